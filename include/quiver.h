@@ -1,0 +1,141 @@
+/*
+ * quiver.h -- C ABI of the MI355X (gfx950) library for the QuIVer query hot path
+ * (arxiv 2605.02171): 2-bit Sign-Magnitude encoding, beam search over a fixed-degree
+ * graph in code space, float32 cosine rerank.
+ *
+ * Conventions for every call
+ *   - "device pointer" = memory on the current HIP device, allocated and owned by the
+ *     caller (the Python binding passes torch tensors' data_ptr()).  The library borrows
+ *     buffers; it never frees or reallocates them.  The caller keeps them alive until the
+ *     work queued on `stream` has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
+ *     work is queued on it and the call returns without waiting, unless stated otherwise.
+ *   - Return value: 0 (QV_OK) or a negative QV_ERR_* code.  Argument errors are found on
+ *     the host before anything is launched; nothing is written in that case.
+ *   - ids are uint32; 0xFFFFFFFF (QV_EMPTY) marks "no node".
+ */
+#ifndef QUIVER_H
+#define QUIVER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QV_EMPTY 0xFFFFFFFFu
+
+#define QV_OK 0
+#define QV_ERR_INVALID_ARG (-1) /* a size or count is out of range                     */
+#define QV_ERR_NULL (-2)        /* a required pointer is NULL                          */
+#define QV_ERR_DIM (-3)         /* d < 1 or d > QV_MAX_DIM                             */
+#define QV_ERR_EF_LT_K (-4)     /* k > ef: the rerank can only return list members     */
+#define QV_ERR_EF_RANGE (-5)    /* ef < 1 or ef > QV_MAX_EF                            */
+#define QV_ERR_WORKSPACE (-6)   /* workspace NULL, misaligned or too small             */
+#define QV_ERR_HIP (-7)         /* a HIP runtime call failed (see qv_last_hip_error)   */
+#define QV_ERR_NOMEM (-8)       /* host allocation failed                              */
+
+#define QV_MAX_DIM 65536
+#define QV_MAX_EF 1024
+#define QV_MAX_DEGREE 4096
+
+/* bits of the per-vector / per-query status words */
+#define QV_STATUS_NONFINITE 1u      /* encode: the vector holds Inf/NaN, its code is unspecified          */
+#define QV_STATUS_VISITED_FULL 2u   /* search: the on-chip visited table filled up; results stay exact,     */
+                                    /* n_dist_evals may count some nodes more than once                     */
+#define QV_STATUS_BAD_EDGE 4u       /* search: an adjacency entry >= n was skipped                          */
+
+/* Words (uint64) per code: 2 * ceil(d / 64); 0 if d is out of range.  Host only. */
+int qv_code_words(int d);
+
+/*
+ * 1. Encode (paper Sec. 3.1, encoding equations): tau = mean_i |x_i| (exact mean),
+ *    pos_i = [x_i > 0], strong_i = [|x_i| > tau].
+ *    x      device, [n][d] float32 row-major.
+ *    codes  device, [n][qv_code_words(d)] uint64: W = ceil(d/64) words of sign bits, then W
+ *           words of magnitude bits; dimension i is bit i%64 (bit 0 = LSB) of word i/64; bits
+ *           of dimensions >= d are 0.
+ *    status device, [n] uint32 or NULL: receives QV_STATUS_NONFINITE or 0 per vector.
+ */
+int qv_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, void* stream);
+
+/*
+ * Test aid (paper Sec. 3.1, Table 1): symmetric distance for pairs of codes,
+ *    out[p] = sum over dimensions with differing sign bits of (1+strong_a)(1+strong_b).
+ *    codes_a/codes_b device code arrays as written by qv_encode; ia/ib device int64 [npairs]
+ *    row indices (the caller guarantees they are in range); out device uint32 [npairs].
+ */
+int qv_bq_distance(const uint64_t* codes_a, const int64_t* ia, const uint64_t* codes_b, const int64_t* ib,
+                   int64_t npairs, int d, uint32_t* out, void* stream);
+
+/*
+ * 2. Load (paper Sec. 4.2: hot data = codes + flat adjacency, cold data = float32 vectors).
+ *    Creates a host-side handle that remembers the borrowed device buffers; copies nothing.
+ *    adj    device, [n][R] uint32, QV_EMPTY = empty slot (rows need not be packed to the left)
+ *    codes  device, [n][qv_code_words(d)] uint64 in qv_encode's layout
+ *    vecs   device, [n][d] float32 (only read by the rerank)
+ *    entry  node every search starts from, < n
+ *    1 <= R <= QV_MAX_DEGREE, 1 <= n < 2^32 - 1.
+ */
+typedef struct qv_index qv_index;
+int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, const uint64_t* codes,
+                  const float* vecs, uint32_t entry);
+void qv_index_free(qv_index* index); /* frees the handle only; NULL is allowed */
+
+/* Optional per-query outputs of qv_search; every pointer is a device pointer or NULL. */
+typedef struct qv_trace {
+    uint32_t* cand_ids;     /* [nq][ef]  final list, sorted by (distance, id); QV_EMPTY padded          */
+    uint32_t* cand_dist;    /* [nq][ef]  their code-space distances; QV_EMPTY padded                    */
+    uint32_t* n_cand;       /* [nq]      length of the final list                                       */
+    uint32_t* n_expanded;   /* [nq]      nodes expanded                                                 */
+    uint32_t* n_dist_evals; /* [nq]      code-space distances computed                                  */
+    uint32_t* visit_order;  /* [nq][visit_cap] ids in the order they were expanded; QV_EMPTY padded     */
+    int64_t visit_cap;      /*           entries per query in visit_order (0 if unused)                 */
+    uint32_t* status;       /* [nq]      QV_STATUS_* bits                                               */
+} qv_trace;
+
+/* Bytes of device scratch qv_search needs for this shape (0 on invalid arguments).  Host only. */
+size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef);
+
+/*
+ * 3. Search (paper Sec. 3.3): per query, encode it once (Stage 1 preamble), run the greedy
+ *    best-first beam search with an ef-wide list keyed by (code distance, id) from the index's
+ *    entry node, then (Stage 2) score every list member with the exact cosine similarity to the
+ *    float32 query and return the best k by (score descending, id ascending).
+ *    queries   device, [nq][d] float32
+ *    ids       device, [nq][k] uint32, QV_EMPTY where the list was shorter than k
+ *    scores    device, [nq][k] float32 cosine (accumulated in double, rounded once), -inf padded;
+ *              a zero-norm query or vector scores 0
+ *    workspace device, 256-byte aligned, >= qv_search_workspace_bytes(nq, d, k, ef); contents
+ *              are scratch (concurrent searches need separate workspaces)
+ *    trace     NULL or a struct of optional outputs
+ *    1 <= k <= ef <= QV_MAX_EF.  nq == 0 is allowed and does nothing.
+ */
+int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids, float* scores,
+              void* workspace, size_t workspace_bytes, const qv_trace* trace, void* stream);
+
+/*
+ * Stage timer: when one is attached, every qv_search on that index records HIP events around its
+ * three stages (query encode, beam search, rerank) on the search's stream.  qv_timer_read waits
+ * for the recorded events and returns milliseconds per stage per recorded call.
+ */
+typedef struct qv_timer qv_timer;
+int qv_timer_create(qv_timer** out, int max_calls);
+void qv_timer_free(qv_timer* t);
+void qv_index_set_timer(qv_index* index, qv_timer* t /* NULL detaches */);
+/* ms: host float [max_calls][3]; returns the number of recorded calls (>= 0) or an error; resets the timer */
+int qv_timer_read(qv_timer* t, float* ms, int max_calls);
+
+/* Tunables of the search kernel (defaults picked from the shape when <= 0).  Host only.
+ *    hash_bits       log2 of the per-query visited-table slots (10..14)
+ *    lanes_per_row   lanes that share one neighbour's code during the gather (power of two, 1..64) */
+int qv_index_set_tuning(qv_index* index, int hash_bits, int lanes_per_row);
+
+const char* qv_strerror(int code);
+const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUIVER_H */

@@ -1,0 +1,255 @@
+"""Thin ctypes binding of ``libquiver_hip.so`` (the C ABI declared in ``include/quiver.h``).
+
+Argument marshalling only: torch tensors supply device memory and the current stream; every step
+of the method runs in the library's HIP kernels.  There is no CPU fallback -- if the shared
+library has not been built, importing this module raises.
+
+Unsigned device arrays are carried in signed torch dtypes of the same width (codes: int64 holding
+uint64 bit patterns; ids, distances, counters: int32 holding uint32).  ``to_numpy_u32`` /
+``to_numpy_u64`` reinterpret them on the host.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libquiver_hip.so")
+
+EMPTY = 0xFFFFFFFF
+STATUS_NONFINITE = 1
+STATUS_VISITED_FULL = 2
+STATUS_BAD_EDGE = 4
+MAX_EF = 1024
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2605_02171_amd.build` "
+        "(hipcc, gfx950). There is no fallback path.")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_P = ctypes.c_void_p
+
+
+class _Trace(ctypes.Structure):
+    _fields_ = [("cand_ids", _P), ("cand_dist", _P), ("n_cand", _P), ("n_expanded", _P), ("n_dist_evals", _P),
+                ("visit_order", _P), ("visit_cap", ctypes.c_int64), ("status", _P)]
+
+
+_lib.qv_code_words.restype = ctypes.c_int
+_lib.qv_code_words.argtypes = [ctypes.c_int]
+_lib.qv_encode.restype = ctypes.c_int
+_lib.qv_encode.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, _P, _P]
+_lib.qv_bq_distance.restype = ctypes.c_int
+_lib.qv_bq_distance.argtypes = [_P, _P, _P, _P, ctypes.c_int64, ctypes.c_int, _P, _P]
+_lib.qv_index_load.restype = ctypes.c_int
+_lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P,
+                               ctypes.c_uint32]
+_lib.qv_index_free.restype = None
+_lib.qv_index_free.argtypes = [_P]
+_lib.qv_index_set_tuning.restype = ctypes.c_int
+_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int]
+_lib.qv_search_workspace_bytes.restype = ctypes.c_size_t
+_lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+_lib.qv_search.restype = ctypes.c_int
+_lib.qv_search.argtypes = [_P, _P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P, ctypes.c_size_t,
+                           ctypes.POINTER(_Trace), _P]
+_lib.qv_timer_create.restype = ctypes.c_int
+_lib.qv_timer_create.argtypes = [ctypes.POINTER(_P), ctypes.c_int]
+_lib.qv_timer_free.restype = None
+_lib.qv_timer_free.argtypes = [_P]
+_lib.qv_index_set_timer.restype = None
+_lib.qv_index_set_timer.argtypes = [_P, _P]
+_lib.qv_timer_read.restype = ctypes.c_int
+_lib.qv_timer_read.argtypes = [_P, _P, ctypes.c_int]
+_lib.qv_strerror.restype = ctypes.c_char_p
+_lib.qv_strerror.argtypes = [ctypes.c_int]
+_lib.qv_last_hip_error.restype = ctypes.c_char_p
+_lib.qv_last_hip_error.argtypes = []
+
+
+class QuiverError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        msg = _lib.qv_strerror(code).decode()
+        hip = _lib.qv_last_hip_error().decode()
+        super().__init__(f"{what}: {msg} ({code})" + (f" [{hip}]" if code == -7 and hip else ""))
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise QuiverError(rc, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype: torch.dtype, what: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a CUDA/HIP torch tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{what} must be contiguous {dtype}, got {t.dtype}")
+    return t
+
+
+def to_numpy_u32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy().view(np.uint32)
+
+
+def to_numpy_u64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().numpy().view(np.uint64)
+
+
+def from_numpy_u32(a: np.ndarray, device="cuda") -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).to(device)
+
+
+def from_numpy_u64(a: np.ndarray, device="cuda") -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).to(device)
+
+
+def code_words(d: int) -> int:
+    return _lib.qv_code_words(int(d))
+
+
+def encode(x: torch.Tensor, want_status: bool = False):
+    """qv_encode: float32 [n, d] on the device -> int64 [n, code_words(d)] (uint64 bit patterns)."""
+    x = _dev(x, torch.float32, "x")
+    if x.dim() != 2:
+        raise ValueError("x must be [n, d]")
+    n, d = x.shape
+    cw = code_words(d)
+    if cw == 0:
+        raise QuiverError(-3, "qv_encode")
+    codes = torch.empty((n, cw), dtype=torch.int64, device=x.device)
+    status = torch.empty((n,), dtype=torch.int32, device=x.device) if want_status else None
+    _check(_lib.qv_encode(x.data_ptr(), n, d, codes.data_ptr(), status.data_ptr() if want_status else None,
+                          _stream()), "qv_encode")
+    return (codes, status) if want_status else codes
+
+
+def bq_distance(codes_a: torch.Tensor, ia: torch.Tensor, codes_b: torch.Tensor, ib: torch.Tensor, d: int):
+    """qv_bq_distance: symmetric code distance for index pairs -> int32 [npairs] (uint32 values)."""
+    codes_a = _dev(codes_a, torch.int64, "codes_a")
+    codes_b = _dev(codes_b, torch.int64, "codes_b")
+    ia = _dev(ia, torch.int64, "ia")
+    ib = _dev(ib, torch.int64, "ib")
+    cw = code_words(d)
+    if codes_a.shape[1] != cw or codes_b.shape[1] != cw or ia.shape != ib.shape:
+        raise ValueError("shape mismatch")
+    if ia.numel() and (int(ia.min()) < 0 or int(ia.max()) >= codes_a.shape[0] or int(ib.min()) < 0 or
+                       int(ib.max()) >= codes_b.shape[0]):
+        raise IndexError("pair index out of range")
+    out = torch.empty(ia.shape, dtype=torch.int32, device=codes_a.device)
+    _check(_lib.qv_bq_distance(codes_a.data_ptr(), ia.data_ptr(), codes_b.data_ptr(), ib.data_ptr(), ia.numel(),
+                               int(d), out.data_ptr(), _stream()), "qv_bq_distance")
+    return out
+
+
+class Timer:
+    """qv_timer: per-stage HIP-event timing of the searches of one index."""
+
+    def __init__(self, max_calls: int):
+        self.max_calls = max_calls
+        h = _P()
+        _check(_lib.qv_timer_create(ctypes.byref(h), max_calls), "qv_timer_create")
+        self._h = h
+
+    def read(self) -> np.ndarray:
+        """Milliseconds [calls, 3] = (query encode, beam search, rerank); waits for the events."""
+        ms = np.zeros((self.max_calls, 3), dtype=np.float32)
+        n = _lib.qv_timer_read(self._h, ms.ctypes.data_as(_P), self.max_calls)
+        if n < 0:
+            raise QuiverError(n, "qv_timer_read")
+        return ms[:n]
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            _lib.qv_timer_free(self._h)
+            self._h = None
+
+
+class Index:
+    """qv_index_load: borrows adj [n, R] (int32/uint32 bits), codes [n, cw] int64, vecs [n, d] float32."""
+
+    def __init__(self, adj: torch.Tensor, codes: torch.Tensor, vecs: torch.Tensor, entry: int):
+        adj = _dev(adj, torch.int32, "adj")
+        codes = _dev(codes, torch.int64, "codes")
+        vecs = _dev(vecs, torch.float32, "vecs")
+        n, d = vecs.shape
+        if adj.shape[0] != n or codes.shape != (n, code_words(d)):
+            raise ValueError("adj/codes/vecs shapes do not agree")
+        self.n, self.d, self.R = n, d, adj.shape[1]
+        self._keep = (adj, codes, vecs)  # the library borrows these buffers
+        h = _P()
+        _check(_lib.qv_index_load(ctypes.byref(h), n, d, self.R, adj.data_ptr(), codes.data_ptr(), vecs.data_ptr(),
+                                  int(entry)), "qv_index_load")
+        self._h = h
+        self._timer = None
+
+    def set_tuning(self, hash_bits: int = 0, lanes_per_row: int = 0) -> None:
+        _check(_lib.qv_index_set_tuning(self._h, hash_bits, lanes_per_row), "qv_index_set_tuning")
+
+    def set_timer(self, timer: Timer | None) -> None:
+        self._timer = timer
+        _lib.qv_index_set_timer(self._h, timer._h if timer else None)
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            _lib.qv_index_free(self._h)
+            self._h = None
+
+
+@dataclass
+class SearchOutput:
+    ids: torch.Tensor                 # [nq, k] int32 (uint32 bits), EMPTY padded
+    scores: torch.Tensor              # [nq, k] float32
+    cand_ids: torch.Tensor | None = None      # [nq, ef]
+    cand_dist: torch.Tensor | None = None     # [nq, ef]
+    n_cand: torch.Tensor | None = None        # [nq]
+    n_expanded: torch.Tensor | None = None
+    n_dist_evals: torch.Tensor | None = None
+    visit_order: torch.Tensor | None = None   # [nq, visit_cap]
+    status: torch.Tensor | None = None
+
+
+def search_workspace_bytes(nq: int, d: int, k: int, ef: int) -> int:
+    return int(_lib.qv_search_workspace_bytes(nq, d, k, ef))
+
+
+def search(index: Index, queries: torch.Tensor, k: int, ef: int, trace: bool = False, visit_cap: int = 0,
+           workspace: torch.Tensor | None = None, out: SearchOutput | None = None) -> SearchOutput:
+    """qv_search: encode queries, beam search in code space, float32 cosine rerank -> top-k."""
+    queries = _dev(queries, torch.float32, "queries")
+    if queries.dim() != 2 or queries.shape[1] != index.d:
+        raise ValueError("queries must be [nq, d]")
+    nq = queries.shape[0]
+    dev = queries.device
+    need = search_workspace_bytes(nq, index.d, k, ef)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+    if out is None:
+        i32 = lambda *s: torch.empty(s, dtype=torch.int32, device=dev)
+        out = SearchOutput(i32(nq, k), torch.empty((nq, k), dtype=torch.float32, device=dev))
+        if trace:
+            out.cand_ids, out.cand_dist = i32(nq, max(ef, 0)), i32(nq, max(ef, 0))
+            out.n_cand, out.n_expanded, out.n_dist_evals, out.status = i32(nq), i32(nq), i32(nq), i32(nq)
+            if visit_cap > 0:
+                out.visit_order = i32(nq, visit_cap)
+    tr = None
+    if out.cand_ids is not None or out.n_expanded is not None or out.visit_order is not None:
+        ptr = lambda t: t.data_ptr() if t is not None else None
+        tr = _Trace(ptr(out.cand_ids), ptr(out.cand_dist), ptr(out.n_cand), ptr(out.n_expanded),
+                    ptr(out.n_dist_evals), ptr(out.visit_order),
+                    out.visit_order.shape[1] if out.visit_order is not None else 0, ptr(out.status))
+    rc = _lib.qv_search(index._h, queries.data_ptr(), nq, int(k), int(ef), out.ids.data_ptr(),
+                        out.scores.data_ptr(), workspace.data_ptr() if workspace is not None else None,
+                        workspace.numel() if workspace is not None else 0,
+                        ctypes.byref(tr) if tr is not None else None, _stream())
+    _check(rc, "qv_search")
+    return out

@@ -1,0 +1,56 @@
+"""Compile the HIP library for gfx950 (in-tree: csrc/*.hip -> libquiver_hip.so)."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libquiver_hip.so")
+SOURCES = ["api.hip", "encode.hip", "search.hip", "rerank.hip"]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-parameter",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _newest_source() -> float:
+    files = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+    files.append(os.path.join(HERE, "..", "include", "quiver.h"))
+    return max(os.path.getmtime(f) for f in files)
+
+
+def is_current() -> bool:
+    return os.path.exists(LIB) and os.path.getmtime(LIB) >= _newest_source()
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    if not force and is_current():
+        return LIB
+    objs = [os.path.join(CSRC, s.replace(".hip", ".o")) for s in SOURCES]
+
+    def compile_one(args):
+        src, obj = args
+        cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
+        # the host pass does not know the device-only target feature; that warning is expected
+        noise = "is not a recognized feature for this target"
+        rest = [l for l in r.stderr.splitlines() if l.strip() and noise not in l]
+        if verbose and rest:
+            print("\n".join(rest), file=sys.stderr)
+
+    with ThreadPoolExecutor(4) as ex:
+        list(ex.map(compile_one, zip(SOURCES, objs)))
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)
+    for o in objs:
+        os.remove(o)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True, verbose=True))

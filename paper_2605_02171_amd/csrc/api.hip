@@ -1,0 +1,234 @@
+// C ABI of the library (see include/quiver.h): argument checks, workspace carving, launches.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/quiver.h"
+#include "kernels.h"
+
+static_assert(QV_STATUS_NONFINITE == qv::QV_STATUS_NONFINITE_BIT, "status bits");
+static_assert(QV_STATUS_VISITED_FULL == qv::QV_STATUS_VISITED_FULL_BIT, "status bits");
+static_assert(QV_STATUS_BAD_EDGE == qv::QV_STATUS_BAD_EDGE_BIT, "status bits");
+static_assert(QV_EMPTY == qv::EMPTY_ID, "empty id");
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e, const char* where) {
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", where, hipGetErrorString(e));
+    return QV_ERR_HIP;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WorkspaceLayout {
+    size_t qcodes, cand_ids, cand_dist, n_cand, total;
+};
+
+WorkspaceLayout layout(int64_t nq, int d, int ef) {
+    WorkspaceLayout L;
+    size_t off = 0;
+    L.qcodes = off;    off = align_up(off + (size_t)nq * qv_code_words(d) * 8, 256);
+    L.cand_ids = off;  off = align_up(off + (size_t)nq * ef * 4, 256);
+    L.cand_dist = off; off = align_up(off + (size_t)nq * ef * 4, 256);
+    L.n_cand = off;    off = align_up(off + (size_t)nq * 4, 256);
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+struct qv_timer {
+    int max_calls;
+    int used;
+    hipEvent_t* ev;  // 4 per call: start, after encode, after search, after rerank
+};
+
+struct qv_index {
+    int64_t n;
+    int d, R;
+    const uint32_t* adj;
+    const uint64_t* codes;
+    const float* vecs;
+    uint32_t entry;
+    int hash_bits;      // <= 0: choose from ef
+    int lanes_per_row;  // <= 0: choose from d
+    qv_timer* timer;
+};
+
+extern "C" {
+
+int qv_code_words(int d) { return (d < 1 || d > QV_MAX_DIM) ? 0 : 2 * ((d + 63) / 64); }
+
+int qv_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (n < 0) return QV_ERR_INVALID_ARG;
+    if (n == 0) return QV_OK;
+    if (!x || !codes) return QV_ERR_NULL;
+    hipError_t e = qv::launch_encode(x, n, d, codes, status, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "encode launch");
+}
+
+int qv_bq_distance(const uint64_t* codes_a, const int64_t* ia, const uint64_t* codes_b, const int64_t* ib,
+                   int64_t npairs, int d, uint32_t* out, void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (npairs < 0) return QV_ERR_INVALID_ARG;
+    if (npairs == 0) return QV_OK;
+    if (!codes_a || !codes_b || !ia || !ib || !out) return QV_ERR_NULL;
+    hipError_t e = qv::launch_bq_distance(codes_a, ia, codes_b, ib, npairs, d, out, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "bq_distance launch");
+}
+
+int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, const uint64_t* codes,
+                  const float* vecs, uint32_t entry) {
+    if (!out) return QV_ERR_NULL;
+    *out = nullptr;
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (n < 1 || n >= 0xFFFFFFFFll || R < 1 || R > QV_MAX_DEGREE || (int64_t)entry >= n) return QV_ERR_INVALID_ARG;
+    if (!adj || !codes || !vecs) return QV_ERR_NULL;
+    qv_index* ix = new (std::nothrow) qv_index;
+    if (!ix) return QV_ERR_NOMEM;
+    ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
+    ix->hash_bits = 0; ix->lanes_per_row = 0; ix->timer = nullptr;
+    *out = ix;
+    return QV_OK;
+}
+
+void qv_index_free(qv_index* index) { delete index; }
+
+int qv_index_set_tuning(qv_index* index, int hash_bits, int lanes_per_row) {
+    if (!index) return QV_ERR_NULL;
+    if (hash_bits > 0 && (hash_bits < 10 || hash_bits > 14)) return QV_ERR_INVALID_ARG;
+    if (lanes_per_row > 0 && (lanes_per_row > 16 || (lanes_per_row & (lanes_per_row - 1)))) return QV_ERR_INVALID_ARG;
+    index->hash_bits = hash_bits;
+    index->lanes_per_row = lanes_per_row;
+    return QV_OK;
+}
+
+size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef) {
+    if (nq < 0 || d < 1 || d > QV_MAX_DIM || ef < 1 || ef > QV_MAX_EF || k < 1 || k > ef) return 0;
+    return layout(nq > 0 ? nq : 1, d, ef).total;
+}
+
+int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids, float* scores,
+              void* workspace, size_t workspace_bytes, const qv_trace* trace, void* stream_) {
+    if (!index) return QV_ERR_NULL;
+    if (nq < 0 || nq > 0x7FFFFFFFll || k < 1) return QV_ERR_INVALID_ARG;
+    if (ef < 1 || ef > QV_MAX_EF) return QV_ERR_EF_RANGE;
+    if (k > ef) return QV_ERR_EF_LT_K;
+    if (trace && trace->visit_order && trace->visit_cap < 1) return QV_ERR_INVALID_ARG;
+    if (nq == 0) return QV_OK;
+    if (!queries || !ids || !scores) return QV_ERR_NULL;
+    const WorkspaceLayout L = layout(nq, index->d, ef);
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < L.total) return QV_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)stream_;
+    char* ws = static_cast<char*>(workspace);
+    uint64_t* qcodes = reinterpret_cast<uint64_t*>(ws + L.qcodes);
+
+    qv_timer* tm = index->timer;
+    hipEvent_t* ev = nullptr;
+    if (tm && tm->used < tm->max_calls) ev = tm->ev + 4 * (size_t)tm->used++;
+    hipError_t e;
+    if (ev && (e = hipEventRecord(ev[0], stream)) != hipSuccess) return hip_fail(e, "event record");
+
+    // Stage 1 preamble: the query's own code
+    e = qv::launch_encode(queries, nq, index->d, qcodes, nullptr, stream);
+    if (e != hipSuccess) return hip_fail(e, "query encode launch");
+    if (ev && (e = hipEventRecord(ev[1], stream)) != hipSuccess) return hip_fail(e, "event record");
+
+    qv::SearchParams sp;
+    sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes;
+    sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
+    if (index->hash_bits > 0) sp.hash_bits = index->hash_bits;
+    else sp.hash_bits = ef <= 16 ? 12 : 13;
+    // the final lists go straight into the caller's trace buffers when there are any
+    sp.cand_ids = trace && trace->cand_ids ? trace->cand_ids : reinterpret_cast<uint32_t*>(ws + L.cand_ids);
+    sp.cand_dist = trace && trace->cand_dist ? trace->cand_dist : reinterpret_cast<uint32_t*>(ws + L.cand_dist);
+    sp.n_cand = trace && trace->n_cand ? trace->n_cand : reinterpret_cast<uint32_t*>(ws + L.n_cand);
+    sp.n_expanded = trace ? trace->n_expanded : nullptr;
+    sp.n_evals = trace ? trace->n_dist_evals : nullptr;
+    sp.status = trace ? trace->status : nullptr;
+    sp.visit_order = trace ? trace->visit_order : nullptr;
+    sp.visit_cap = trace && trace->visit_order ? trace->visit_cap : 0;
+    e = qv::launch_beam_search(sp, index->lanes_per_row, stream);
+    if (e != hipSuccess) return hip_fail(e, "beam search launch");
+    if (ev && (e = hipEventRecord(ev[2], stream)) != hipSuccess) return hip_fail(e, "event record");
+
+    qv::RerankParams rp;
+    rp.queries = queries; rp.vecs = index->vecs; rp.cand_ids = sp.cand_ids; rp.n_cand = sp.n_cand;
+    rp.nq = nq; rp.d = index->d; rp.ef = ef; rp.k = k; rp.ids = ids; rp.scores = scores;
+    e = qv::launch_rerank(rp, stream);
+    if (e != hipSuccess) return hip_fail(e, "rerank launch");
+    if (ev && (e = hipEventRecord(ev[3], stream)) != hipSuccess) return hip_fail(e, "event record");
+
+    return QV_OK;
+}
+
+int qv_timer_create(qv_timer** out, int max_calls) {
+    if (!out) return QV_ERR_NULL;
+    *out = nullptr;
+    if (max_calls < 1 || max_calls > 65536) return QV_ERR_INVALID_ARG;
+    qv_timer* t = new (std::nothrow) qv_timer;
+    if (!t) return QV_ERR_NOMEM;
+    t->max_calls = max_calls; t->used = 0;
+    t->ev = new (std::nothrow) hipEvent_t[4 * (size_t)max_calls];
+    if (!t->ev) { delete t; return QV_ERR_NOMEM; }
+    for (int i = 0; i < 4 * max_calls; ++i) {
+        hipError_t e = hipEventCreate(&t->ev[i]);
+        if (e != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(t->ev[j]);
+            delete[] t->ev; delete t;
+            return hip_fail(e, "event create");
+        }
+    }
+    *out = t;
+    return QV_OK;
+}
+
+void qv_timer_free(qv_timer* t) {
+    if (!t) return;
+    for (int i = 0; i < 4 * t->max_calls; ++i) (void)hipEventDestroy(t->ev[i]);
+    delete[] t->ev;
+    delete t;
+}
+
+void qv_index_set_timer(qv_index* index, qv_timer* t) { if (index) index->timer = t; }
+
+int qv_timer_read(qv_timer* t, float* ms, int max_calls) {
+    if (!t || !ms) return QV_ERR_NULL;
+    int n = t->used < max_calls ? t->used : max_calls;
+    for (int c = 0; c < n; ++c) {
+        hipEvent_t* ev = t->ev + 4 * (size_t)c;
+        hipError_t e = hipEventSynchronize(ev[3]);
+        if (e != hipSuccess) return hip_fail(e, "event synchronize");
+        for (int s = 0; s < 3; ++s) {
+            e = hipEventElapsedTime(&ms[3 * c + s], ev[s], ev[s + 1]);
+            if (e != hipSuccess) return hip_fail(e, "event elapsed");
+        }
+    }
+    t->used = 0;
+    return n;
+}
+
+const char* qv_strerror(int code) {
+    switch (code) {
+        case QV_OK: return "ok";
+        case QV_ERR_INVALID_ARG: return "a size or count is out of range";
+        case QV_ERR_NULL: return "a required pointer is NULL";
+        case QV_ERR_DIM: return "dimension out of range";
+        case QV_ERR_EF_LT_K: return "k is larger than ef";
+        case QV_ERR_EF_RANGE: return "ef out of range";
+        case QV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case QV_ERR_HIP: return "HIP runtime error";
+        case QV_ERR_NOMEM: return "host allocation failed";
+        default: return "unknown error code";
+    }
+}
+
+const char* qv_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qv {
+
+constexpr uint32_t EMPTY_ID = 0xFFFFFFFFu;
+constexpr uint32_t QV_STATUS_NONFINITE_BIT = 1u;
+constexpr uint32_t QV_STATUS_VISITED_FULL_BIT = 2u;
+constexpr uint32_t QV_STATUS_BAD_EDGE_BIT = 4u;
+
+struct SearchParams {
+    const uint32_t* adj;     // [n][R]
+    const uint64_t* codes;   // [n][2*nw]
+    const uint64_t* qcodes;  // [nq][2*nw]
+    int64_t n;
+    int64_t nq;
+    int nw;                  // 64-bit words per bit-plane
+    int R;
+    uint32_t entry;
+    int ef;
+    int hash_bits;           // log2(slots) of the visited table
+    // outputs
+    uint32_t* cand_ids;      // [nq][ef]
+    uint32_t* cand_dist;     // [nq][ef]
+    uint32_t* n_cand;        // [nq]
+    uint32_t* n_expanded;    // [nq] or null
+    uint32_t* n_evals;       // [nq] or null
+    uint32_t* status;        // [nq] or null
+    uint32_t* visit_order;   // [nq][visit_cap] or null
+    int64_t visit_cap;
+};
+
+struct RerankParams {
+    const float* queries;    // [nq][d]
+    const float* vecs;       // [n][d]
+    const uint32_t* cand_ids;  // [nq][ef]
+    const uint32_t* n_cand;  // [nq]
+    int64_t nq;
+    int d;
+    int ef;
+    int k;
+    uint32_t* ids;           // [nq][k]
+    float* scores;           // [nq][k]
+};
+
+hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, hipStream_t stream);
+hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
+                              int64_t npairs, int d, uint32_t* out, hipStream_t stream);
+// lanes_per_row: 0 = pick from the shape
+hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
+size_t beam_search_lds_bytes(int nw, int hash_bits);
+hipError_t launch_rerank(const RerankParams& p, hipStream_t stream);
+
+}  // namespace qv

@@ -1,0 +1,236 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from tests import util
+from workloads import datagen, graph
+
+pytestmark = pytest.mark.gpu
+E = util.E
+
+
+@pytest.fixture(scope="module")
+def qv():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2605_02171_amd as m
+    return m
+
+
+def _special_vectors(d, rng):
+    rows = []
+    rows.append(np.full(d, 0.1, dtype=np.float32))                        # all equal: nothing is strong
+    rows.append(np.zeros(d, dtype=np.float32))
+    x = np.zeros(d, dtype=np.float32); x[::2] = -0.0; rows.append(x)
+    base = np.float32(0.123456).view(np.uint32)
+    ulps = rng.integers(-3, 4, size=d)
+    x = (base + ulps).astype(np.uint32).view(np.float32) * rng.choice([-1.0, 1.0], size=d).astype(np.float32)
+    rows.append(x.astype(np.float32))                                     # many values within ulps of the mean
+    x = np.full(d, 0.3, dtype=np.float32); x[d // 2] = np.nextafter(np.float32(0.3), np.float32(1)); rows.append(x)
+    expo = rng.integers(-140, 100, size=d)
+    x = (rng.standard_normal(d) * np.exp2(expo.astype(np.float64))).astype(np.float32)
+    rows.append(np.where(np.isfinite(x), x, 1.0).astype(np.float32))      # huge dynamic range
+    x = rng.standard_normal(d).astype(np.float32) * np.float32(1e-41); rows.append(x)   # subnormals only
+    x = np.full(d, 1e-45, dtype=np.float32); x[0] = 2e-45; rows.append(x)
+    x = np.full(d, 3.0e38, dtype=np.float32); x[-1] = -3.4e38; rows.append(x)            # sum overflows float32
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("d", [1, 2, 63, 64, 65, 100, 128, 200, 384, 512, 768, 1000, 3072])
+def test_encode_bit_exact(qv, d):
+    rng = np.random.default_rng(100 + d)
+    n = 523  # not a multiple of the vectors-per-workgroup
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    x[:64] *= np.exp2(rng.integers(-30, 30, size=(64, 1))).astype(np.float32)
+    x = np.concatenate([x, _special_vectors(d, rng)])
+    want = oracle.encode(x, threads=8)
+    got, status = qv.encode(torch.from_numpy(x).cuda(), want_status=True)
+    assert (qv.to_numpy_u64(got) == want).all()
+    assert (qv.to_numpy_u32(status) == 0).all()
+
+
+def test_encode_workloads_bit_exact(qv):
+    for name, n in (("C1", 10_000), ("C2", 20_000), ("C3", 20_000), ("C4", 5_000), ("C5", 20_000)):
+        w = datagen.scaled(name, n=n, nq=10)
+        x = datagen.make_base(w)
+        want = oracle.encode(x, threads=8)
+        got = qv.encode(torch.from_numpy(x).cuda())
+        assert (qv.to_numpy_u64(got) == want).all(), name
+
+
+def test_encode_flags_non_finite_and_empty_input(qv):
+    x = np.ones((9, 70), dtype=np.float32)
+    x[2, 5] = np.inf
+    x[7, 69] = np.nan
+    codes, status = qv.encode(torch.from_numpy(x).cuda(), want_status=True)
+    st = qv.to_numpy_u32(status)
+    assert st.tolist() == [0, 0, 1, 0, 0, 0, 0, 1, 0]
+    ok = [0, 1, 3, 4, 5, 6, 8]
+    assert (qv.to_numpy_u64(codes)[ok] == oracle.encode(x[ok])).all()
+    empty = qv.encode(torch.empty((0, 70), dtype=torch.float32, device="cuda"))
+    assert empty.shape == (0, 4)
+
+
+@pytest.mark.parametrize("d", [1, 64, 100, 768, 3072])
+def test_bq_distance_bit_exact(qv, d):
+    rng = np.random.default_rng(7 + d)
+    xa = rng.standard_normal((300, d)).astype(np.float32)
+    xb = rng.standard_normal((200, d)).astype(np.float32)
+    ca, cb = oracle.encode(xa), oracle.encode(xb)
+    ia = rng.integers(0, 300, size=5000)
+    ib = rng.integers(0, 200, size=5000)
+    want = oracle.sm_distance_pairs(ca, ia, cb, ib, d)
+    got = qv.bq_distance(qv.from_numpy_u64(ca), torch.from_numpy(ia).cuda(), qv.from_numpy_u64(cb),
+                         torch.from_numpy(ib).cuda(), d)
+    assert (qv.to_numpy_u32(got) == want).all()
+    # identity and symmetry on the device as well
+    same = qv.bq_distance(qv.from_numpy_u64(ca), torch.from_numpy(ia).cuda(), qv.from_numpy_u64(ca),
+                          torch.from_numpy(ia).cuda(), d)
+    assert (qv.to_numpy_u32(same) == 0).all()
+
+
+def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, hash_bits=0, lanes=0):
+    codes = oracle.encode(x, threads=8)
+    ref = oracle.search(q, adj, codes, x, entry, k, ef, visit_cap=visit_cap, threads=8)
+    xd = torch.from_numpy(x).cuda()
+    gcodes = qv.encode(xd)
+    assert (qv.to_numpy_u64(gcodes) == codes).all()
+    index = qv.Index(qv.from_numpy_u32(adj), gcodes, xd, entry)
+    if hash_bits or lanes:
+        index.set_tuning(hash_bits, lanes)
+    out = qv.search(index, torch.from_numpy(q).cuda(), k, ef, trace=True, visit_cap=visit_cap)
+    torch.cuda.synchronize()
+    return ref, out
+
+
+def _assert_search_equal(qv, ref, out, exact_counters=True):
+    assert (qv.to_numpy_u32(out.cand_ids) == ref.cand_ids).all()
+    assert (qv.to_numpy_u32(out.cand_dist) == ref.cand_dist).all()
+    assert (qv.to_numpy_u32(out.n_cand) == ref.n_cand).all()
+    assert (qv.to_numpy_u32(out.n_expanded) == ref.n_expanded).all()
+    assert (qv.to_numpy_u32(out.visit_order) == ref.visit_order).all()
+    ev = qv.to_numpy_u32(out.n_dist_evals)
+    st = qv.to_numpy_u32(out.status)
+    if exact_counters:
+        assert (st == 0).all()
+        assert (ev == ref.n_dist_evals).all()
+    else:
+        assert (ev >= ref.n_dist_evals).all()
+        assert (ev[(st & 2) == 0] == ref.n_dist_evals[(st & 2) == 0]).all()
+    util.assert_topk_matches(qv.to_numpy_u32(out.ids), out.scores.cpu().numpy(), ref.ids, ref.scores)
+
+
+def test_search_tiny_workload_all_queries(qv):
+    w = datagen.WORKLOADS["C1"]
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, w.R, w.L, w.alpha)
+    ref, out = _run_both(qv, x, q, adj, entry, w.k, 64)
+    _assert_search_equal(qv, ref, out)
+
+
+@pytest.mark.parametrize("d,R,ef,k", [
+    (100, 10, 1, 1), (100, 10, 5, 5), (128, 32, 64, 10), (200, 70, 65, 10), (64, 64, 128, 128),
+    (384, 64, 16, 10), (768, 64, 32, 10), (512, 17, 200, 50), (1024, 64, 64, 10), (130, 130, 300, 7),
+])
+def test_search_random_graphs_bit_exact(qv, d, R, ef, k):
+    rng = np.random.default_rng(d * 1000 + R)
+    n, nq = 3000, 37
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    adj = datagen.random_regular_graph(n, R, seed=d + R, fill=0.85)
+    ref, out = _run_both(qv, x, q, adj, entry=5, k=k, ef=ef, visit_cap=400)
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 4, 8, 16])
+def test_search_every_gather_width(qv, lanes):
+    w = datagen.scaled("C2", n=6000, nq=25)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 64, 1.2)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, 48, lanes=lanes)
+    _assert_search_equal(qv, ref, out)
+
+
+def test_search_full_visited_table_keeps_results_exact(qv):
+    # a deliberately small visited table: it fills up, nodes get re-evaluated, the lists must not change
+    w = datagen.scaled("C2", n=20_000, nq=40)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 64, 1.2)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, 128, visit_cap=300, hash_bits=10)
+    st = qv.to_numpy_u32(out.status)
+    assert (st & 2).any(), "the test is meant to overflow the table"
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+def test_search_degenerate_graphs(qv):
+    rng = np.random.default_rng(3)
+    n, d = 500, 96
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((9, d)).astype(np.float32)
+    # no edges at all: the list is the entry node
+    adj = np.full((n, 8), E, dtype=np.uint32)
+    ref, out = _run_both(qv, x, q, adj, entry=7, k=3, ef=8)
+    _assert_search_equal(qv, ref, out)
+    assert (qv.to_numpy_u32(out.ids)[:, 0] == 7).all() and (qv.to_numpy_u32(out.ids)[:, 1:] == E).all()
+    # self loops, duplicate edges, a chain
+    adj = np.full((n, 8), E, dtype=np.uint32)
+    adj[:, 0] = np.arange(n)
+    adj[:, 1] = (np.arange(n) + 1) % n
+    adj[:, 2] = adj[:, 1]
+    adj[:, 5] = (np.arange(n) * 7 + 3) % n
+    ref, out = _run_both(qv, x, q, adj, entry=0, k=4, ef=10, visit_cap=600)
+    _assert_search_equal(qv, ref, out)
+    # a single node
+    ref, out = _run_both(qv, x[:1], q, np.full((1, 4), E, dtype=np.uint32), entry=0, k=1, ef=4)
+    _assert_search_equal(qv, ref, out)
+
+
+def test_search_skips_edges_to_missing_nodes_and_reports_them(qv):
+    rng = np.random.default_rng(4)
+    n, d = 300, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((5, d)).astype(np.float32)
+    adj = datagen.random_regular_graph(n, 6, seed=1)
+    bad = adj.copy()
+    bad[:, 3] = np.uint32(n + 5)                       # every row has one edge to a node that does not exist
+    clean = adj.copy()
+    clean[:, 3] = E
+    codes = oracle.encode(x)
+    ref = oracle.search(q, clean, codes, x, 0, 5, 20, visit_cap=300)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(bad), qv.encode(xd), xd, 0)
+    out = qv.search(index, torch.from_numpy(q).cuda(), 5, 20, trace=True, visit_cap=300)
+    assert (qv.to_numpy_u32(out.cand_ids) == ref.cand_ids).all()
+    assert (qv.to_numpy_u32(out.status) & 4).all()
+
+
+def test_empty_batch_and_argument_errors(qv):
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((50, 64)).astype(np.float32)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(datagen.random_regular_graph(50, 4, 1)), qv.encode(xd), xd, 0)
+    out = qv.search(index, torch.empty((0, 64), dtype=torch.float32, device="cuda"), 3, 8)
+    assert out.ids.shape == (0, 3)
+    qd = xd[:4].contiguous()
+    with pytest.raises(qv.QuiverError) as e:
+        qv.search(index, qd, 9, 8)
+    assert e.value.code == -4
+    with pytest.raises(qv.QuiverError) as e:
+        qv.search(index, qd, 1, qv.MAX_EF + 1)
+    assert e.value.code == -5
+    with pytest.raises(qv.QuiverError) as e:
+        qv.search(index, qd, 1, 8, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.code == -6
+    with pytest.raises(qv.QuiverError):
+        qv.Index(qv.from_numpy_u32(datagen.random_regular_graph(50, 4, 1)), qv.encode(xd), xd, 50)
+
+
+@pytest.mark.parametrize("name,n,ef", [("C2", 50_000, 64), ("C2", 50_000, 128), ("C3", 50_000, 64),
+                                       ("C4", 12_000, 64), ("C5", 50_000, 64)])
+def test_search_workload_shapes_reduced_n(qv, name, n, ef):
+    w = datagen.scaled(name, n=n, nq=200)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, w.R, 64, w.alpha)
+    ref, out = _run_both(qv, x, q, adj, entry, w.k, ef, visit_cap=400)
+    _assert_search_equal(qv, ref, out)
