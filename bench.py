@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the QuIVer query hot path on one MI355X.
+
+A "step" is one batch through qv_search (query encode -> code-space beam search -> float32 cosine
+rerank) for all queries of the workload, inputs resident in HBM.  The default workload is the 768-d,
+1M-vector, ef=64 configuration the metric is quoted on.  Prints ONE JSON line on stdout; progress
+goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(msg: str) -> None:
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def ground_truth(xd, qd, k, metric):
+    """Exact float32 top-k on the GPU (chunked matmul; the only dense contraction in this repo)."""
+    import torch
+    n = xd.shape[0]
+    best_v = torch.full((qd.shape[0], k), -float("inf"), device=qd.device)
+    best_i = torch.zeros((qd.shape[0], k), dtype=torch.int64, device=qd.device)
+    qn = qd / qd.norm(dim=1, keepdim=True).clamp_min(1e-30) if metric == "cosine" else qd
+    q2 = (qd * qd).sum(1, keepdim=True)
+    for s in range(0, n, 131072):
+        xb = xd[s:s + 131072]
+        if metric == "cosine":
+            sim = qn @ (xb / xb.norm(dim=1, keepdim=True).clamp_min(1e-30)).T
+        else:
+            sim = -(q2 - 2.0 * (qd @ xb.T) + (xb * xb).sum(1)[None, :])
+        v, i = sim.topk(k, dim=1)
+        cat_v = torch.cat([best_v, v], 1)
+        cat_i = torch.cat([best_i, i + s], 1)
+        best_v, sel = cat_v.topk(k, dim=1)
+        best_i = cat_i.gather(1, sel)
+    return best_i.cpu().numpy()
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
+    ap.add_argument("--nq", type=int, default=0)
+    ap.add_argument("--ef", type=int, default=64)
+    ap.add_argument("--hash-bits", type=int, default=0)
+    ap.add_argument("--lanes-per-row", type=int, default=0)
+    ap.add_argument("--cpu-sample", type=int, default=10000, help="queries the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (queries would be sharded over replicas of the index; "
+              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2605_02171_amd as qv
+    from workloads import datagen, graph
+
+    torch.cuda.set_device(0)
+    w = datagen.scaled(args.workload, n=args.n or None, nq=args.nq or None)
+    ef, k = args.ef, w.k
+    t0 = time.time()
+    x = datagen.make_base(w)
+    q = datagen.make_queries(w)
+    log(f"workload {w.name}: n={w.n} d={w.d} nq={w.nq} generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    adj, entry = graph.cached_graph(f"{w.name}_{w.n}", x, w.R, w.L, w.alpha,
+                                    progress_path=os.path.join(ROOT, "gpurun_out", "bench_progress.log"))
+    t_graph = time.time() - t0
+    log(f"graph R={w.R} L={w.L} alpha={w.alpha} ready in {t_graph:.1f}s (host, {graph.host_threads()} threads)")
+
+    xd = torch.from_numpy(x).cuda()
+    qd = torch.from_numpy(q).cuda()
+    adjd = qv.from_numpy_u32(adj)
+
+    # base encode (index-build side of the hot path): timed on its own
+    codes = qv.encode(xd)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        codes = qv.encode(xd)
+    e1.record()
+    torch.cuda.synchronize()
+    enc_ms = e0.elapsed_time(e1) / 5
+    enc_bytes = w.n * (4 * w.d + w.d // 4)
+    log(f"encode base: {enc_ms:.3f} ms, {enc_bytes / enc_ms / 1e6:.0f} GB/s")
+
+    index = qv.Index(adjd, codes, xd, entry)
+    if args.hash_bits or args.lanes_per_row:
+        index.set_tuning(args.hash_bits, args.lanes_per_row)
+    ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
+
+    # one traced pass: counters for the algorithmic-byte model, results for recall / parity
+    traced = qv.search(index, qd, k, ef, trace=True, workspace=ws)
+    torch.cuda.synchronize()
+    n_exp = qv.to_numpy_u32(traced.n_expanded).astype(np.int64)
+    n_eval = qv.to_numpy_u32(traced.n_dist_evals).astype(np.int64)
+    n_cand = qv.to_numpy_u32(traced.n_cand).astype(np.int64)
+    status = qv.to_numpy_u32(traced.status)
+    ids_gpu = qv.to_numpy_u32(traced.ids)
+    code_b = w.d // 4 if w.d % 64 == 0 else 16 * ((w.d + 63) // 64)
+    search_bytes = int(4 * w.R * n_exp.sum() + code_b * n_eval.sum() + code_b * w.nq + 8 * ef * w.nq)
+    rerank_bytes = int(4 * w.d * n_cand.sum() + 4 * w.d * w.nq + 8 * k * w.nq)
+    encq_bytes = int(w.nq * (4 * w.d + code_b))
+    log(f"per query: expanded {n_exp.mean():.1f}, distance evals {n_eval.mean():.0f} (max {n_eval.max()}), "
+        f"visited-table overflows {(status & 2 != 0).sum()}")
+
+    # timed region
+    out = qv.SearchOutput(traced.ids, traced.scores)
+    for _ in range(args.warmup):
+        qv.search(index, qd, k, ef, workspace=ws, out=out)
+    timer = qv.Timer(args.steps)
+    index.set_timer(timer)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        qv.search(index, qd, k, ef, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    stage_ms = timer.read()
+    index.set_timer(None)
+    ms_per_step = wall * 1e3 / args.steps
+    qps = w.nq / (wall / args.steps)
+    search_ms = float(stage_ms[:, 1].mean())
+    log(f"{ms_per_step:.3f} ms/step, {qps:.0f} QPS; stages (ms): encode {stage_ms[:, 0].mean():.3f}, "
+        f"search {search_ms:.3f}, rerank {stage_ms[:, 2].mean():.3f}")
+
+    gt = ground_truth(xd, qd, k, w.metric)
+    recall = float(np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids_gpu, gt)]) / k)
+    log(f"Recall@{k} = {recall:.4f}")
+
+    # CPU oracle on a bounded sample of the same queries, all host threads
+    cpu = None
+    parity = None
+    if args.cpu_sample > 0:
+        import oracle
+        threads = graph.host_threads()
+        ns = min(args.cpu_sample, w.nq)
+        t0 = time.time()
+        ocodes = oracle.encode(x, threads=threads)
+        t_enc = time.time() - t0
+        t0 = time.time()
+        ref = oracle.search(q[:ns], adj, ocodes, x, entry, k, ef, threads=threads)
+        t_cpu = time.time() - t0
+        parity = bool((ref.cand_ids == qv.to_numpy_u32(traced.cand_ids)[:ns]).all() and
+                      (ref.cand_dist == qv.to_numpy_u32(traced.cand_dist)[:ns]).all() and
+                      (ref.n_dist_evals == n_eval[:ns]).all() and
+                      (ocodes == qv.to_numpy_u64(codes)).all())
+        orecall = float(np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ref.ids, gt[:ns])]) / k)
+        cpu = {"value": ns / t_cpu, "unit": "queries/s", "cores": threads, "kind": "oracle",
+               "sample": f"first {ns} of the {w.nq} queries, same graph/codes/vectors; search+rerank wall time "
+                         f"{t_cpu:.2f}s ({threads} threads); base encode by the oracle took {t_enc:.1f}s (not included)",
+               "recall_at_10": orecall}
+        log(f"oracle: {ns / t_cpu:.0f} QPS on {threads} threads, recall {orecall:.4f}, parity with GPU: {parity}")
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}_ef{ef}.json")
+    if os.path.exists(tpath) and not args.n and not args.nq:
+        with open(tpath) as f:
+            traffic = json.load(f).get("search_kernel_hbm_bytes_per_launch")
+
+    achieved = search_bytes / (search_ms * 1e-3) / 1e9
+    line = {
+        "metric": "QPS at Recall@10 (ef=%d), 1M x 768 on 1 MI355X" % ef if w.name == "C2" and not args.n
+                  else f"QPS at Recall@10 (ef={ef})",
+        "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64 popcount (search), f64-accumulated f32 (rerank)", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n} x {w.d} {w.kind} unit-norm vectors, {w.nq} queries, "
+                               f"graph R={w.R} L={w.L} alpha={w.alpha}, k={k}, ef={ef}"},
+        "recall_at_10": recall,
+        "bq_dist_evals_per_s": float(n_eval.sum() / (search_ms * 1e-3)),
+        "stage_ms": {"query_encode": float(stage_ms[:, 0].mean()), "beam_search": search_ms,
+                     "rerank": float(stage_ms[:, 2].mean())},
+        "algorithmic_bytes_per_step": {"query_encode": encq_bytes, "beam_search": search_bytes,
+                                       "rerank": rerank_bytes},
+        "whole_path_GBps": (encq_bytes + search_bytes + rerank_bytes) / (ms_per_step * 1e-3) / 1e9,
+        "encode_base": {"ms": enc_ms, "GBps": enc_bytes / enc_ms / 1e6},
+        "graph_build_s": t_graph,
+        "parity_with_oracle_on_sample": parity,
+        "roofline": {"kernel": "beam_search_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
