@@ -59,6 +59,9 @@ def main() -> int:
     ap.add_argument("--ef", type=int, default=64)
     ap.add_argument("--hash-bits", type=int, default=0)
     ap.add_argument("--lanes-per-row", type=int, default=0)
+    ap.add_argument("--table-format", type=int, default=0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one elementwise copy kernel (1 GiB read + 1 GiB write) to calibrate byte counters")
     ap.add_argument("--cpu-sample", type=int, default=10000, help="queries the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -102,8 +105,8 @@ def main() -> int:
     log(f"encode base: {enc_ms:.3f} ms, {enc_bytes / enc_ms / 1e6:.0f} GB/s")
 
     index = qv.Index(adjd, codes, xd, entry)
-    if args.hash_bits or args.lanes_per_row:
-        index.set_tuning(args.hash_bits, args.lanes_per_row)
+    if args.hash_bits or args.lanes_per_row or args.table_format:
+        index.set_tuning(args.hash_bits, args.lanes_per_row, args.table_format)
     ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
 
     # one traced pass: counters for the algorithmic-byte model, results for recall / parity
@@ -119,7 +122,9 @@ def main() -> int:
     rerank_bytes = int(4 * w.d * n_cand.sum() + 4 * w.d * w.nq + 8 * k * w.nq)
     encq_bytes = int(w.nq * (4 * w.d + code_b))
     log(f"per query: expanded {n_exp.mean():.1f}, distance evals {n_eval.mean():.0f} (max {n_eval.max()}), "
-        f"visited-table overflows {(status & 2 != 0).sum()}")
+        f"visited-table overflows {(status & 2 != 0).sum()}; expanded p50/p90/p99/max = "
+        f"{np.percentile(n_exp, 50):.0f}/{np.percentile(n_exp, 90):.0f}/{np.percentile(n_exp, 99):.0f}/{n_exp.max()}; "
+        f"evals p50/p90/p99 = {np.percentile(n_eval, 50):.0f}/{np.percentile(n_eval, 90):.0f}/{np.percentile(n_eval, 99):.0f}")
 
     # timed region
     out = qv.SearchOutput(traced.ids, traced.scores)
@@ -140,6 +145,14 @@ def main() -> int:
     search_ms = float(stage_ms[:, 1].mean())
     log(f"{ms_per_step:.3f} ms/step, {qps:.0f} QPS; stages (ms): encode {stage_ms[:, 0].mean():.3f}, "
         f"search {search_ms:.3f}, rerank {stage_ms[:, 2].mean():.3f}")
+
+    if args.calib_copy:
+        a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 1.0, out=b)  # one vectorized elementwise kernel: reads 2^30 B, writes 2^30 B
+        torch.cuda.synchronize()
+        del a, b
 
     gt = ground_truth(xd, qd, k, w.metric)
     recall = float(np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids_gpu, gt)]) / k)

@@ -127,10 +127,12 @@ void qv_index_set_timer(qv_index* index, qv_timer* t /* NULL detaches */);
 /* ms: host float [max_calls][3]; returns the number of recorded calls (>= 0) or an error; resets the timer */
 int qv_timer_read(qv_timer* t, float* ms, int max_calls);
 
-/* Tunables of the search kernel (defaults picked from the shape when <= 0).  Host only.
- *    hash_bits       log2 of the per-query visited-table slots (10..14)
- *    lanes_per_row   lanes that share one neighbour's code during the gather (power of two, 1..64) */
-int qv_index_set_tuning(qv_index* index, int hash_bits, int lanes_per_row);
+/* Tunables of the search kernel (defaults picked from the shape when 0).  Host only.
+ *    hash_bits       log2 of the per-query visited-table slots (10..15)
+ *    lanes_per_row   lanes that share one neighbour's code during the gather (1, 2, 4, 8 or 16)
+ *    table_format    0: 16-bit visited-table entries whenever the graph is small enough for them
+ *                    (about 4M nodes at 8192 slots), else 32-bit; 32: always 32-bit entries */
+int qv_index_set_tuning(qv_index* index, int hash_bits, int lanes_per_row, int table_format);
 
 const char* qv_strerror(int code);
 const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */

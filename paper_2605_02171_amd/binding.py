@@ -52,7 +52,7 @@ _lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int,
 _lib.qv_index_free.restype = None
 _lib.qv_index_free.argtypes = [_P]
 _lib.qv_index_set_tuning.restype = ctypes.c_int
-_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int]
+_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search_workspace_bytes.restype = ctypes.c_size_t
 _lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search.restype = ctypes.c_int
@@ -192,8 +192,8 @@ class Index:
         self._h = h
         self._timer = None
 
-    def set_tuning(self, hash_bits: int = 0, lanes_per_row: int = 0) -> None:
-        _check(_lib.qv_index_set_tuning(self._h, hash_bits, lanes_per_row), "qv_index_set_tuning")
+    def set_tuning(self, hash_bits: int = 0, lanes_per_row: int = 0, table_format: int = 0) -> None:
+        _check(_lib.qv_index_set_tuning(self._h, hash_bits, lanes_per_row, table_format), "qv_index_set_tuning")
 
     def set_timer(self, timer: Timer | None) -> None:
         self._timer = timer

@@ -4,21 +4,25 @@
 // Mapping to gfx950: one 64-lane wavefront per query, one wavefront per workgroup.
 //   * candidate list ("pool"): ef sorted 64-bit keys held in registers, entry e in lane e%64,
 //     register e/64.  key = dist << 33 | id << 1 | expanded, so integer order is (dist, id) order.
-//   * visited set: exact open-addressing table of 32-bit ids in LDS (linear probing, LDS
-//     compare-and-swap).  When it is nearly full it stops taking new ids; from then on a node may
-//     be evaluated twice, which cannot change the list (see the note at merge_key) and is reported
-//     in the status word.
-//   * expansion: lane j reads adj[u][j] (one coalesced row), lanes filter their ids through the
-//     visited table, survivors are compacted into LDS, then G lanes cooperate on one neighbour's
-//     code: lane s of a group loads words s, s+G, ... of both bit-planes (8*G contiguous bytes
-//     per group per load instruction), XOR/AND/OR + popcount, and a G-lane butterfly adds the
-//     partial sums.  64/G neighbours are in flight per pass.
-//   * merge: new keys below the current worst are inserted one by one with a ballot rank and a
-//     one-lane shift.  The pool after an expansion is the ef smallest keys of (old pool U new
-//     keys), which does not depend on insertion order, so expanding all neighbours at once
-//     reproduces the sequential algorithm exactly.
+//   * visited set: exact bucketed hash table of ids in LDS (one 16-byte bucket per probe, LDS
+//     compare-and-swap to claim a slot).  When it is nearly full it stops taking new ids; from
+//     then on a node may be evaluated twice, which cannot change the list (see merge_new_keys)
+//     and is reported in the status word.
+//   * expansion: lane j reads adj[u][j] (one coalesced row; the row of the runner-up is loaded one
+//     expansion ahead), lanes filter their ids through the visited table, survivors are compacted
+//     into LDS, then G lanes cooperate on one neighbour's code: lane s of a group loads words s,
+//     s+G, ... of both bit-planes (8*G contiguous bytes per group per load instruction); all loads
+//     of an expansion are issued before the first popcount.  XOR/AND/OR + popcount per lane, then
+//     a reduce-scatter over the G lanes leaves each lane with the distance of one neighbour.
+//   * merge: every new key below the current worst gets its final position from two counts (pool
+//     keys below it, new keys below it), every pool key moves up by the number of new keys below
+//     it, and one scatter through LDS puts everything in place.  The pool after an expansion is
+//     the ef smallest keys of (old pool U new keys); that set does not depend on the order in
+//     which neighbours are considered, so expanding all neighbours at once reproduces the
+//     sequential algorithm exactly.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "kernels.h"
 
@@ -37,24 +41,79 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int l) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-__device__ __forceinline__ uint64_t shfl_up1_64(uint64_t v) {
-    uint32_t lo = (uint32_t)__shfl_up((int)(uint32_t)v, 1);
-    uint32_t hi = (uint32_t)__shfl_up((int)(uint32_t)(v >> 32), 1);
-    return ((uint64_t)hi << 32) | lo;
+// value of the lane whose index differs in bit 0 / bit 1 (data-parallel primitive, no LDS traffic)
+__device__ __forceinline__ uint32_t quad_xor1(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);  // quad_perm:[1,0,3,2]
+}
+__device__ __forceinline__ uint32_t quad_xor2(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // quad_perm:[2,3,0,1]
 }
 
-__device__ __forceinline__ uint32_t hash_slot(uint32_t v, int bits) { return (v * 2654435761u) >> (32 - bits); }
-
-// Insert id v (or only look it up when !may_insert).  Returns true when v was not in the table.
-__device__ __forceinline__ bool visited_test_and_set(uint32_t* tab, uint32_t mask, int bits, uint32_t v,
-                                                     bool may_insert) {
-    uint32_t h = hash_slot(v, bits);
+// ---------------------------------------------------------------------------------------------
+// Visited set, 32-bit entries: buckets of four ids; an id lives in the first bucket, counting from
+// its home bucket, that had a free slot when it arrived.  Slots are never freed, so a lookup may
+// stop at the first bucket that still has a free slot.
+// Returns true when v was not in the table (and is now, if may_insert).
+__device__ __forceinline__ bool visited32_test_and_set(uint32_t* tab, uint32_t bucket_mask, int bucket_bits,
+                                                       uint32_t v, bool may_insert) {
+    uint32_t b = (v * 2654435761u) >> (32 - bucket_bits);
     for (;;) {
-        uint32_t cur = may_insert ? atomicCAS(&tab[h], EMPTY_ID, v) : tab[h];
-        if (cur == EMPTY_ID) return true;   // was free: v is new (and now stored if may_insert)
-        if (cur == v) return false;
-        h = (h + 1) & mask;                 // the table is never allowed to fill up, so this ends
+        uint32_t* bp = tab + b * 4;
+        const uint4 s = *reinterpret_cast<const uint4*>(bp);
+        if (s.x == v || s.y == v || s.z == v || s.w == v) return false;
+        const int e = s.x == EMPTY_ID ? 0 : (s.y == EMPTY_ID ? 1 : (s.z == EMPTY_ID ? 2 : (s.w == EMPTY_ID ? 3 : -1)));
+        if (e < 0) {
+            b = (b + 1) & bucket_mask;  // the table is never allowed to fill up, so this ends
+            continue;
+        }
+        if (!may_insert) return true;
+        const uint32_t old = atomicCAS(bp + e, EMPTY_ID, v);
+        if (old == EMPTY_ID) return true;
+        if (old == v) return false;     // another lane holds the same id and was first
+        // another id took the slot: look at this bucket again
     }
+}
+
+// Visited set, 16-bit entries, for graphs of up to a few million nodes (half the LDS per query).
+// An id is split as v = r0 * 65535 + t0; the table is cut into `regions` equal parts of B buckets,
+// v lives in part (r0 + g(t0)) mod regions (g spreads consecutive ids over the parts) and stores
+// only the tag t0 < 65535, so (part, tag) identifies v exactly; 0xFFFF = free.  Buckets hold eight
+// tags (16 bytes); probing runs over the buckets of the part.  `failed` is raised when the part has
+// no room left.
+__device__ __forceinline__ uint32_t any_zero_half(uint32_t x) { return (x - 0x00010001u) & ~x & 0x80008000u; }
+
+__device__ __forceinline__ bool visited16_test_and_set(uint32_t* tab32, uint32_t regions, uint32_t B, uint32_t v,
+                                                       bool may_insert, bool& failed) {
+    const uint32_t r0 = v / 65535u;
+    const uint32_t t0 = v - r0 * 65535u;
+    uint32_t r = r0 + ((((t0 * 40503u) & 0xFFFFu) * regions) >> 16);
+    if (r >= regions) r -= regions;
+    const uint32_t base = r * B;
+    uint32_t hb = (((v * 2654435761u) >> 16) * B) >> 16;
+    const uint32_t pat = t0 * 0x00010001u;
+    for (uint32_t probes = 0; probes < B;) {
+        uint32_t* bp = tab32 + (base + hb) * 4;
+        const uint4 s = *reinterpret_cast<const uint4*>(bp);
+        if (any_zero_half(s.x ^ pat) | any_zero_half(s.y ^ pat) | any_zero_half(s.z ^ pat) | any_zero_half(s.w ^ pat))
+            return false;
+        int e = -1;
+        uint32_t word = 0;
+        if (any_zero_half(~s.x)) { e = 0; word = s.x; }
+        else if (any_zero_half(~s.y)) { e = 1; word = s.y; }
+        else if (any_zero_half(~s.z)) { e = 2; word = s.z; }
+        else if (any_zero_half(~s.w)) { e = 3; word = s.w; }
+        if (e < 0) {
+            hb = hb + 1 == B ? 0 : hb + 1;
+            ++probes;
+            continue;
+        }
+        if (!may_insert) return true;
+        const uint32_t want = (word & 0xFFFFu) == 0xFFFFu ? ((word & 0xFFFF0000u) | t0) : ((word & 0xFFFFu) | (t0 << 16));
+        if (atomicCAS(bp + e, word, want) == word) return true;
+        // the word changed under us: look at this bucket again
+    }
+    failed = true;
+    return true;  // no room: the node is evaluated (possibly again); the merge drops duplicates
 }
 
 template <int P>
@@ -63,60 +122,101 @@ struct Pool {
     int size;
 };
 
-// Insert one key into the sorted pool (wave-uniform arguments).  A key whose (dist, id) is already
-// present is dropped: that only happens after the visited table stopped taking ids, and then a
+// Merge the candidate keys `mine` (one per lane, KEY_NONE where a lane has none) into the sorted pool.
+// With check_dup, a key whose (dist, id) is already in the pool, or is held by a lower lane too, is
+// dropped first: that only happens after the visited table stopped taking ids, and then a
 // re-evaluated node is either still in the pool (dropped here) or was rejected/evicted before, in
-// which case it is above the current worst key (the worst key never grows once the pool is full)
-// and never reaches this function.
+// which case it is above the current worst key -- the worst key never grows once the pool is full --
+// and is filtered out by the first test below.
 template <int P>
-__device__ __forceinline__ void merge_key(Pool<P>& pool, uint64_t nk, int ef, int lane, bool check_dup) {
-    int pos = 0;
-    bool dup = false;
+__device__ __forceinline__ void merge_new_keys(Pool<P>& pool, uint64_t mine, int ef, int lane, bool check_dup,
+                                               uint64_t* skeys) {
+    uint64_t worst = KEY_NONE;  // key of the last slot: KEY_NONE while the pool has room
+#pragma unroll
+    for (int r = 0; r < P; ++r)
+        if (r == ((ef - 1) >> 6)) worst = readlane64(pool.key[r], (ef - 1) & 63);
+    uint64_t qual = __ballot(mine < worst);
+    if (check_dup && qual) {
+        uint64_t scan = qual;
+        while (scan) {
+            const int j = __ffsll((unsigned long long)scan) - 1;
+            scan &= scan - 1;
+            const uint64_t nk = readlane64(mine, j);
+            bool dup = lane < j && mine == nk;
+#pragma unroll
+            for (int r = 0; r < P; ++r) dup |= (pool.key[r] >> 1) == (nk >> 1);
+            if (__any(dup)) qual &= ~(1ull << j);
+        }
+    }
+    if (!qual) return;
+    const bool is_new = (qual >> lane) & 1ull;
+
+    uint32_t up[P];       // pool entries: number of new keys below them
+    uint32_t my_pos = 0;  // new keys: number of pool keys and of other new keys below them
+#pragma unroll
+    for (int r = 0; r < P; ++r) up[r] = 0;
+    uint64_t scan = qual;
+    while (scan) {
+        const int j = __ffsll((unsigned long long)scan) - 1;
+        scan &= scan - 1;
+        const uint64_t nk = readlane64(mine, j);
+        uint32_t below = 0;
+#pragma unroll
+        for (int r = 0; r < P; ++r) {
+            const bool lt = pool.key[r] < nk;
+            below += (uint32_t)__popcll(__ballot(lt));
+            up[r] += lt ? 0u : 1u;
+        }
+        if (lane == j) my_pos += below;
+        my_pos += (is_new && nk < mine) ? 1u : 0u;
+    }
+    const int new_size = min(ef, pool.size + (int)__popcll(qual));
+    wave_sync();
 #pragma unroll
     for (int r = 0; r < P; ++r) {
-        pos += __popcll(__ballot(pool.key[r] < nk));
-        if (check_dup) dup |= (pool.key[r] >> 1) == (nk >> 1);
+        const uint32_t np = (uint32_t)(r * 64 + lane) + up[r];
+        if (pool.key[r] != KEY_NONE && np < (uint32_t)ef) skeys[np] = pool.key[r];
     }
-    if (check_dup && __any(dup)) return;
-    if (pos >= ef) return;
+    if (is_new && my_pos < (uint32_t)ef) skeys[my_pos] = mine;
+    wave_sync();
 #pragma unroll
-    for (int r = P - 1; r >= 0; --r) {
-        uint64_t up = shfl_up1_64(pool.key[r]);
-        if (r > 0) {
-            uint64_t carry = readlane64(pool.key[r - 1], 63);
-            if (lane == 0) up = carry;
-        }
-        int e = r * 64 + lane;
-        if (e == pos) pool.key[r] = nk;
-        else if (e > pos) pool.key[r] = up;   // lane 0 of register 0 is never > pos unless pos < 0
+    for (int r = 0; r < P; ++r) {
+        const int e = r * 64 + lane;
+        pool.key[r] = e < new_size ? skeys[e] : KEY_NONE;
     }
-    if (pool.size < ef) pool.size++;
-    // entries at index >= ef are not part of the pool
-    if ((ef & 63) || ef < 64 * P) {
-#pragma unroll
-        for (int r = 0; r < P; ++r)
-            if (r * 64 + lane >= ef) pool.key[r] = KEY_NONE;
-    }
+    pool.size = new_size;
 }
 
-template <int NW_T, int G, int P>
+template <int NW_T, int G, int P, bool NARROW>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
     const int NW = NW_T > 0 ? NW_T : p.nw;
     const int hbits = p.hash_bits;
-    const uint32_t cap = 1u << hbits, hmask = cap - 1;
-    const uint32_t vis_limit = cap - (cap >> 3) - 64;  // stop inserting at 7/8 full
+    const uint32_t cap = 1u << hbits;   // slots (32-bit each, or 16-bit when NARROW)
+    const uint32_t vis_regions = p.vis_regions, vis_B = p.vis_region_buckets;
+    const uint32_t vis_used = NARROW ? vis_regions * vis_B * 8 : cap;
+    const uint32_t vis_limit = vis_used - (vis_used >> 2) - 64;  // stop inserting at 3/4 full
+    const uint32_t tab_words = NARROW ? cap >> 1 : cap;
+    const int bucket_bits = hbits - 2;
+    const uint32_t bucket_mask = (1u << bucket_bits) - 1;
     uint32_t* tab = smem;
-    uint32_t* list = tab + cap;       // [64] compacted new neighbour ids
-    uint32_t* dlist = list + 64;      // [64] their distances
-    uint64_t* qlds = reinterpret_cast<uint64_t*>(dlist + 64);  // [2*NW] query code (generic path)
+    uint32_t* list = tab + tab_words;  // [64] compacted new neighbour ids
+    uint32_t* dlist = list + 64;       // [64] their distances (generic gather path)
+    uint64_t* skeys = reinterpret_cast<uint64_t*>(dlist + 64);  // [64*P + 64] merge scatter area
+    uint64_t* qlds = skeys + 64 * P + 64;                      // [2*NW] query code (generic path)
 
-    for (uint32_t i = lane; i < cap; i += 64) tab[i] = EMPTY_ID;
+    for (uint32_t i = lane * 4; i < tab_words; i += 256)
+        *reinterpret_cast<uint4*>(tab + i) = make_uint4(EMPTY_ID, EMPTY_ID, EMPTY_ID, EMPTY_ID);
 
-    constexpr int RPP = 64 / G;                       // neighbour rows per pass
+    constexpr int RPP = 64 / G;  // neighbour rows per pass
     constexpr int KW = NW_T > 0 ? (NW_T + G - 1) / G : 1;
+    // passes whose loads are in flight together: all G of them unless that needs > 32 x 64-bit registers
+    constexpr int BATCH = (2 * KW * G <= 32) ? G : (32 / (2 * KW) > 0 ? 32 / (2 * KW) : 1);
+    // with all passes in one batch and groups inside a quad, the lane sums are combined by a
+    // reduce-scatter over data-parallel primitives and never go through LDS
+    constexpr bool QUAD_REDUCE = NW_T > 0 && BATCH == G && (G == 2 || G == 4);
     const int sub = lane % G, grp = lane / G;
     const uint64_t* qsrc = p.qcodes + q * (int64_t)(2 * NW);
     uint64_t qp[KW], qs[KW];
@@ -146,90 +246,175 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     // distances of list[0..m) -> merge into the pool
     auto process_list = [&](int m) {
         wave_sync();  // list[] written by other lanes
-        for (int base = 0; base < m; base += RPP) {
-            int ri = base + grp;
-            uint32_t c1 = 0, c2 = 0, c3 = 0;
-            if (ri < m) {
-                const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW);
-                if constexpr (NW_T > 0) {
-                    uint64_t pv[KW], sv[KW];
+        uint64_t mine = KEY_NONE;
+        if constexpr (QUAD_REDUCE) {
+            // pass b handles row b*RPP + grp; all loads first, then the arithmetic
+            uint64_t pv[G][KW], sv[G][KW];
+#pragma unroll
+            for (int b = 0; b < G; ++b) {
+                const int ri = b * RPP + grp;
+                if (ri < m) {
+                    const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW_T);
 #pragma unroll
                     for (int i = 0; i < KW; ++i) {
                         int w = sub + i * G;
-                        pv[i] = w < NW_T ? row[w] : 0ull;
-                        sv[i] = w < NW_T ? row[NW_T + w] : 0ull;
-                    }
-#pragma unroll
-                    for (int i = 0; i < KW; ++i) {
-                        uint64_t X = pv[i] ^ qp[i];
-                        c1 += __popcll(X);
-                        c2 += __popcll(X & (sv[i] | qs[i]));
-                        c3 += __popcll(X & sv[i] & qs[i]);
+                        pv[b][i] = w < NW_T ? row[w] : 0ull;
+                        sv[b][i] = w < NW_T ? row[NW_T + w] : 0ull;
                     }
                 } else {
-                    for (int w = sub; w < NW; w += G) {
-                        uint64_t X = row[w] ^ qlds[w];
-                        uint64_t sv = row[NW + w], sq = qlds[NW + w];
-                        c1 += __popcll(X);
-                        c2 += __popcll(X & (sv | sq));
-                        c3 += __popcll(X & sv & sq);
-                    }
+#pragma unroll
+                    for (int i = 0; i < KW; ++i) pv[b][i] = sv[b][i] = 0ull;
                 }
             }
-            uint32_t dist = c1 + c2 + 2u * c3;
+            uint32_t part[G];
 #pragma unroll
-            for (int off = G >> 1; off >= 1; off >>= 1) dist += __shfl_xor((int)dist, off);
-            if (sub == 0 && ri < m) dlist[ri] = dist;
+            for (int b = 0; b < G; ++b) {
+                uint32_t c1 = 0, c2 = 0, c3 = 0;
+                if (b * RPP < m) {  // wave-uniform
+#pragma unroll
+                    for (int i = 0; i < KW; ++i) {
+                        uint64_t X = pv[b][i] ^ qp[i];
+                        c1 += __popcll(X);
+                        c2 += __popcll(X & (sv[b][i] | qs[i]));
+                        c3 += __popcll(X & sv[b][i] & qs[i]);
+                    }
+                }
+                part[b] = c1 + c2 + 2u * c3;
+            }
+            // reduce-scatter: afterwards lane `sub` holds the full sum of pass my_b
+            uint32_t dist;
+            int my_b;
+            if constexpr (G == 2) {
+                const bool hi = sub & 1;
+                dist = (hi ? part[1] : part[0]) + quad_xor1(hi ? part[0] : part[1]);
+                my_b = hi ? 1 : 0;
+            } else {
+                const bool o1 = sub & 1, o2 = sub & 2;
+                uint32_t k0 = (o1 ? part[2] : part[0]) + quad_xor1(o1 ? part[0] : part[2]);
+                uint32_t k1 = (o1 ? part[3] : part[1]) + quad_xor1(o1 ? part[1] : part[3]);
+                dist = (o2 ? k1 : k0) + quad_xor2(o2 ? k0 : k1);
+                my_b = (o1 ? 2 : 0) + (o2 ? 1 : 0);
+            }
+            const int my_ri = my_b * RPP + grp;
+            if (my_ri < m) mine = ((uint64_t)dist << 33) | ((uint64_t)list[my_ri] << 1);
+        } else {
+            if constexpr (NW_T > 0) {
+                for (int base = 0; base < m; base += RPP * BATCH) {
+                    uint64_t pv[BATCH][KW], sv[BATCH][KW];
+#pragma unroll
+                    for (int b = 0; b < BATCH; ++b) {
+                        int ri = base + b * RPP + grp;
+                        if (ri < m) {
+                            const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW_T);
+#pragma unroll
+                            for (int i = 0; i < KW; ++i) {
+                                int w = sub + i * G;
+                                pv[b][i] = w < NW_T ? row[w] : 0ull;
+                                sv[b][i] = w < NW_T ? row[NW_T + w] : 0ull;
+                            }
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < KW; ++i) pv[b][i] = sv[b][i] = 0ull;
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < BATCH; ++b) {
+                        int ri = base + b * RPP + grp;
+                        if (base + b * RPP < m) {  // wave-uniform
+                            uint32_t c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+                            for (int i = 0; i < KW; ++i) {
+                                uint64_t X = pv[b][i] ^ qp[i];
+                                c1 += __popcll(X);
+                                c2 += __popcll(X & (sv[b][i] | qs[i]));
+                                c3 += __popcll(X & sv[b][i] & qs[i]);
+                            }
+                            uint32_t dist = c1 + c2 + 2u * c3;
+#pragma unroll
+                            for (int off = G >> 1; off >= 1; off >>= 1) dist += __shfl_xor((int)dist, off);
+                            if (sub == 0 && ri < m) dlist[ri] = dist;
+                        }
+                    }
+                }
+            } else {
+                for (int base = 0; base < m; base += RPP) {
+                    int ri = base + grp;
+                    uint32_t c1 = 0, c2 = 0, c3 = 0;
+                    if (ri < m) {
+                        const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW);
+                        for (int w = sub; w < NW; w += G) {
+                            uint64_t X = row[w] ^ qlds[w];
+                            uint64_t sv = row[NW + w], sq = qlds[NW + w];
+                            c1 += __popcll(X);
+                            c2 += __popcll(X & (sv | sq));
+                            c3 += __popcll(X & sv & sq);
+                        }
+                    }
+                    uint32_t dist = c1 + c2 + 2u * c3;
+#pragma unroll
+                    for (int off = G >> 1; off >= 1; off >>= 1) dist += __shfl_xor((int)dist, off);
+                    if (sub == 0 && ri < m) dlist[ri] = dist;
+                }
+            }
+            wave_sync();
+            if (lane < m) mine = ((uint64_t)dlist[lane] << 33) | ((uint64_t)list[lane] << 1);
         }
-        wave_sync();
         n_eval += (uint32_t)m;
-        uint64_t mine = KEY_NONE;
-        if (lane < m) mine = ((uint64_t)dlist[lane] << 33) | ((uint64_t)list[lane] << 1);
-        // worst key currently in a full pool; KEY_NONE while there is room
-        uint64_t worst = KEY_NONE;
-#pragma unroll
-        for (int r = 0; r < P; ++r)
-            if (r == ((ef - 1) >> 6)) worst = readlane64(pool.key[r], (ef - 1) & 63);
-        uint64_t todo = __ballot(mine < worst);
-        while (todo) {
-            int j = __ffsll((unsigned long long)todo) - 1;
-            todo &= todo - 1;
-            uint64_t nk = readlane64(mine, j);
-            merge_key<P>(pool, nk, ef, lane, vis_full);
-        }
+        merge_new_keys<P>(pool, mine, ef, lane, vis_full, skeys);
     };
 
     // the entry node
     if (lane == 0) {
         list[0] = p.entry;
-        visited_test_and_set(tab, hmask, hbits, p.entry, true);
+        bool ignore = false;
+        if constexpr (NARROW) visited16_test_and_set(tab, vis_regions, vis_B, p.entry, true, ignore);
+        else visited32_test_and_set(tab, bucket_mask, bucket_bits, p.entry, true);
     }
     n_vis = 1;
     process_list(1);
 
+    // adjacency row (first 64 slots) of the runner-up, loaded ahead of time: when the next expansion
+    // picks that node -- the usual case once the pool has settled -- its row is already here
+    uint32_t pre_uid = EMPTY_ID, pre_v = EMPTY_ID;
     for (;;) {
-        // best unexpanded entry
-        uint32_t uid = EMPTY_ID;
-        bool found = false;
+        // best unexpanded entry, and the one after it
+        uint32_t uid = EMPTY_ID, uid2 = EMPTY_ID;
+        int n_found = 0;
 #pragma unroll
         for (int r = 0; r < P; ++r) {
-            if (!found) {
+            if (n_found < 2) {
                 uint64_t open = __ballot(pool.key[r] != KEY_NONE && !(pool.key[r] & 1ull));
-                if (open) {
+                if (open && n_found == 0) {
                     int l = __ffsll((unsigned long long)open) - 1;
                     uid = (uint32_t)(readlane64(pool.key[r], l) >> 1);
                     if (lane == l) pool.key[r] |= 1ull;
-                    found = true;
+                    open &= open - 1;
+                    n_found = 1;
+                }
+                if (open && n_found == 1) {
+                    int l = __ffsll((unsigned long long)open) - 1;
+                    uid2 = (uint32_t)(readlane64(pool.key[r], l) >> 1);
+                    n_found = 2;
                 }
             }
         }
-        if (!found) break;
+        if (n_found == 0) break;
         if (order && lane == 0 && (int64_t)n_exp < p.visit_cap) order[n_exp] = uid;
         n_exp++;
+        const bool have_row = uid == pre_uid;
+        const uint32_t first_v = pre_v;
+        if (uid2 != EMPTY_ID && uid2 != pre_uid) {
+            pre_v = lane < p.R ? p.adj[(int64_t)uid2 * p.R + lane] : EMPTY_ID;
+            pre_uid = uid2;
+        } else if (uid2 == EMPTY_ID) {
+            pre_uid = EMPTY_ID;
+        }
 
         const uint32_t* arow = p.adj + (int64_t)uid * p.R;
         for (int c = 0; c < p.R; c += 64) {
-            uint32_t v = (c + lane < p.R) ? arow[c + lane] : EMPTY_ID;
+            uint32_t v;
+            if (c == 0 && have_row) v = first_v;
+            else v = (c + lane < p.R) ? arow[c + lane] : EMPTY_ID;
             bool valid = v != EMPTY_ID;
             if (valid && (int64_t)v >= p.n) { valid = false; status |= QV_STATUS_BAD_EDGE_BIT; }
             int n_valid = __popcll(__ballot(valid));
@@ -237,13 +422,23 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                 vis_full = true;
                 status |= QV_STATUS_VISITED_FULL_BIT;
             }
-            bool fresh = valid && visited_test_and_set(tab, hmask, hbits, v, !vis_full);
             // (with a full table two lanes holding the same id both count as new here; the
             // duplicate check at merge time drops the second one)
+            bool fresh = false;
+            if constexpr (NARROW) {
+                bool failed = false;
+                if (valid) fresh = visited16_test_and_set(tab, vis_regions, vis_B, v, !vis_full, failed);
+                if (__any(failed)) {  // one part of the table is full: stop inserting altogether
+                    vis_full = true;
+                    status |= QV_STATUS_VISITED_FULL_BIT;
+                }
+            } else {
+                fresh = valid && visited32_test_and_set(tab, bucket_mask, bucket_bits, v, !vis_full);
+            }
             uint64_t fm = __ballot(fresh);
             int m = __popcll(fm);
             if (m == 0) continue;
-            if (!vis_full) n_vis += (uint32_t)m;
+            n_vis += (uint32_t)m;
             wave_sync();  // previous readers of list[] are done
             if (fresh) list[__popcll(fm & ((1ull << lane) - 1ull))] = v;
             process_list(m);
@@ -274,14 +469,15 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     }
 }
 
-size_t beam_search_lds_bytes(int nw, int hash_bits) {
-    return ((size_t)1 << hash_bits) * 4 + 64 * 4 * 2 + (size_t)nw * 16 + 16;
+size_t beam_search_lds_bytes(int nw, int hash_bits, bool narrow, int ef) {
+    const int P = (ef + 63) / 64 <= 1 ? 1 : ((ef + 63) / 64 <= 2 ? 2 : ((ef + 63) / 64 <= 4 ? 4 : ((ef + 63) / 64 <= 8 ? 8 : 16)));
+    return ((size_t)1 << hash_bits) * (narrow ? 2 : 4) + 64 * 4 * 2 + (size_t)(64 * P + 64) * 8 + (size_t)nw * 16 + 16;
 }
 
-template <int NW_T, int G, int P>
+template <int NW_T, int G, int P, bool NARROW>
 static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
-    size_t lds = beam_search_lds_bytes(p.nw, p.hash_bits);
-    auto kern = beam_search_kernel<NW_T, G, P>;
+    size_t lds = beam_search_lds_bytes(p.nw, p.hash_bits, NARROW, p.ef);
+    auto kern = beam_search_kernel<NW_T, G, P, NARROW>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -291,14 +487,19 @@ static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <int NW_T, int G, int P>
+static hipError_t launch_n(const SearchParams& p, hipStream_t stream) {
+    return p.vis_regions > 0 ? launch_one<NW_T, G, P, true>(p, stream) : launch_one<NW_T, G, P, false>(p, stream);
+}
+
 template <int NW_T, int G>
 static hipError_t launch_p(const SearchParams& p, hipStream_t stream) {
     int P = (p.ef + 63) / 64;
-    if (P <= 1) return launch_one<NW_T, G, 1>(p, stream);
-    if (P <= 2) return launch_one<NW_T, G, 2>(p, stream);
-    if (P <= 4) return launch_one<NW_T, G, 4>(p, stream);
-    if (P <= 8) return launch_one<NW_T, G, 8>(p, stream);
-    return launch_one<NW_T, G, 16>(p, stream);
+    if (P <= 1) return launch_n<NW_T, G, 1>(p, stream);
+    if (P <= 2) return launch_n<NW_T, G, 2>(p, stream);
+    if (P <= 4) return launch_n<NW_T, G, 4>(p, stream);
+    if (P <= 8) return launch_n<NW_T, G, 8>(p, stream);
+    return launch_n<NW_T, G, 16>(p, stream);
 }
 
 template <int NW_T>
@@ -314,11 +515,23 @@ static hipError_t launch_g(const SearchParams& p, int g, hipStream_t stream) {
 }
 
 static int default_lanes_per_row(int nw) {
-    if (nw <= 2) return 2;
-    if (nw <= 6) return 2;
-    if (nw <= 12) return 4;
+    if (nw <= 8) return 2;
+    if (nw <= 16) return 4;
     if (nw <= 24) return 8;
     return 16;
+}
+
+// Picks the visited-table format: 16-bit entries when every part of the table keeps >= 16 buckets.
+void plan_visited_table(SearchParams& p, bool allow_narrow) {
+    const uint32_t regions = (uint32_t)((p.n + 65534) / 65535);
+    const uint32_t buckets = (1u << p.hash_bits) / 8;
+    if (allow_narrow && buckets / regions >= 16) {
+        p.vis_regions = regions;
+        p.vis_region_buckets = buckets / regions;
+    } else {
+        p.vis_regions = 0;
+        p.vis_region_buckets = 0;
+    }
 }
 
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream) {

@@ -90,15 +90,15 @@ def test_bq_distance_bit_exact(qv, d):
     assert (qv.to_numpy_u32(same) == 0).all()
 
 
-def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, hash_bits=0, lanes=0):
+def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, hash_bits=0, lanes=0, table_format=0):
     codes = oracle.encode(x, threads=8)
     ref = oracle.search(q, adj, codes, x, entry, k, ef, visit_cap=visit_cap, threads=8)
     xd = torch.from_numpy(x).cuda()
     gcodes = qv.encode(xd)
     assert (qv.to_numpy_u64(gcodes) == codes).all()
     index = qv.Index(qv.from_numpy_u32(adj), gcodes, xd, entry)
-    if hash_bits or lanes:
-        index.set_tuning(hash_bits, lanes)
+    if hash_bits or lanes or table_format:
+        index.set_tuning(hash_bits, lanes, table_format)
     out = qv.search(index, torch.from_numpy(q).cuda(), k, ef, trace=True, visit_cap=visit_cap)
     torch.cuda.synchronize()
     return ref, out
@@ -152,14 +152,45 @@ def test_search_every_gather_width(qv, lanes):
     _assert_search_equal(qv, ref, out)
 
 
-def test_search_full_visited_table_keeps_results_exact(qv):
+@pytest.mark.parametrize("table_format", [0, 32])
+def test_search_full_visited_table_keeps_results_exact(qv, table_format):
     # a deliberately small visited table: it fills up, nodes get re-evaluated, the lists must not change
     w = datagen.scaled("C2", n=20_000, nq=40)
     x, q = datagen.make_base(w), datagen.make_queries(w)
     adj, entry = graph.build_graph(x, 64, 64, 1.2)
-    ref, out = _run_both(qv, x, q, adj, entry, 10, 128, visit_cap=300, hash_bits=10)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, 128, visit_cap=300, hash_bits=10, table_format=table_format)
     st = qv.to_numpy_u32(out.status)
     assert (st & 2).any(), "the test is meant to overflow the table"
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+@pytest.mark.parametrize("table_format", [0, 32])
+def test_search_both_visited_table_formats(qv, table_format):
+    w = datagen.scaled("C3", n=30_000, nq=60)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 48, 1.2)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, 64, visit_cap=300, table_format=table_format)
+    _assert_search_equal(qv, ref, out)
+
+
+def test_search_visited_table_in_several_parts(qv):
+    # n > 65535: the 16-bit table is cut into parts (three here, of a size that is not a power of two)
+    w = datagen.scaled("C3", n=150_000, nq=80)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 32, 1.2)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, 64, visit_cap=300)
+    _assert_search_equal(qv, ref, out)
+
+
+def test_search_small_table_in_eight_parts_overflows_gracefully(qv):
+    # 1024 slots in 8 parts of 128: single parts fill up before the table does
+    rng = np.random.default_rng(77)
+    n, d = 500_000, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((64, d)).astype(np.float32)
+    adj = datagen.random_regular_graph(n, 16, seed=9)
+    ref, out = _run_both(qv, x, q, adj, entry=11, k=10, ef=128, visit_cap=300, hash_bits=10)
+    assert (qv.to_numpy_u32(out.status) & 2).all()
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
