@@ -1,0 +1,119 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+All base vectors are encoded on both sides and compared bit for bit; the whole query batch runs on the
+GPU, a sample of it runs through the CPU oracle and is compared element by element; the rest of the
+batch is checked through properties that hold for any correct run.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from tests import util
+from workloads import datagen, graph
+
+pytestmark = pytest.mark.gpu
+E = util.E
+
+
+@pytest.fixture(scope="module")
+def qv():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2605_02171_amd as m
+    return m
+
+
+def _exact_topk(xd, qd, k, metric):
+    n = xd.shape[0]
+    best_v = torch.full((qd.shape[0], k), -float("inf"), device=qd.device)
+    best_i = torch.zeros((qd.shape[0], k), dtype=torch.int64, device=qd.device)
+    qn = qd / qd.norm(dim=1, keepdim=True).clamp_min(1e-30)
+    for s in range(0, n, 65536):
+        xb = xd[s:s + 65536]
+        if metric == "cosine":
+            sim = qn @ (xb / xb.norm(dim=1, keepdim=True).clamp_min(1e-30)).T
+        else:
+            sim = -((qd * qd).sum(1, keepdim=True) - 2.0 * (qd @ xb.T) + (xb * xb).sum(1)[None, :])
+        v, i = sim.topk(k, dim=1)
+        best_v, sel = torch.cat([best_v, v], 1).topk(k, dim=1)
+        best_i = torch.cat([best_i, i + s], 1).gather(1, sel)
+    return best_i.cpu().numpy()
+
+
+def _full_case(qv, name, efs, n_sample, L=None):
+    w = datagen.WORKLOADS[name]
+    t0 = time.time()
+    util.note(f"{name}: generating {w.n} x {w.d}")
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    util.note(f"{name}: building graph R={w.R} L={L or w.L}")
+    adj, entry = graph.cached_graph(f"{name}_{w.n}", x, w.R, L or w.L, w.alpha, progress_path=util.progress_path())
+    util.note(f"{name}: inputs ready after {time.time() - t0:.0f}s; oracle encodes")
+    threads = graph.host_threads()
+    codes = oracle.encode(x, threads=threads)
+
+    xd = torch.from_numpy(x).cuda()
+    gcodes = qv.encode(xd)
+    assert (qv.to_numpy_u64(gcodes) == codes).all(), "codes differ"
+    index = qv.Index(qv.from_numpy_u32(adj), gcodes, xd, entry)
+    qd = torch.from_numpy(q).cuda()
+    gt = _exact_topk(xd, qd[:n_sample], w.k, w.metric)
+    for ef in efs:
+        util.note(f"{name}: ef={ef} oracle on {n_sample} queries")
+        ref = oracle.search(q[:n_sample], adj, codes, x, entry, w.k, ef, visit_cap=256, threads=threads)
+        out = qv.search(index, qd, w.k, ef, trace=True, visit_cap=256)   # the whole batch, as bench.py runs it
+        torch.cuda.synchronize()
+        cid = qv.to_numpy_u32(out.cand_ids)
+        cds = qv.to_numpy_u32(out.cand_dist)
+        st = qv.to_numpy_u32(out.status)
+        ev = qv.to_numpy_u32(out.n_dist_evals)
+        # sampled queries: element by element
+        s = slice(0, n_sample)
+        assert (cid[s] == ref.cand_ids).all()
+        assert (cds[s] == ref.cand_dist).all()
+        assert (qv.to_numpy_u32(out.n_cand)[s] == ref.n_cand).all()
+        assert (qv.to_numpy_u32(out.n_expanded)[s] == ref.n_expanded).all()
+        assert (qv.to_numpy_u32(out.visit_order)[s] == ref.visit_order).all()
+        exact = (st[s] & 2) == 0
+        assert (ev[s][exact] == ref.n_dist_evals[exact]).all() and (ev[s] >= ref.n_dist_evals).all()
+        assert exact.mean() > 0.9
+        ids = qv.to_numpy_u32(out.ids)
+        util.assert_topk_matches(ids[s], out.scores.cpu().numpy()[s], ref.ids, ref.scores)
+        r_gpu, r_ref = util.recall_at_k(ids[s], gt), util.recall_at_k(ref.ids, gt)
+        assert abs(r_gpu - r_ref) <= 1.0 / gt.size + 1e-12    # one tie-swap at the k boundary at most
+        util.note(f"{name}: ef={ef} sample parity ok; recall@{w.k} gpu {r_gpu:.4f} oracle {r_ref:.4f}")
+        # every query of the batch: list sorted by (dist, id), ids distinct and in range, results inside the list
+        keys = (cds.astype(np.int64) << 32) | cid.astype(np.int64)
+        assert (np.diff(keys, axis=1) > 0).all()
+        assert (cid < w.n).all() and (st & ~np.uint32(2) == 0).all()
+        assert (qv.to_numpy_u32(out.n_cand) == ef).all()
+        member = (ids[:, :, None] == cid[:, None, :]).any(axis=2)
+        assert member.all()
+        sc = out.scores.cpu().numpy()
+        assert (np.diff(sc, axis=1) <= 0).all() and np.isfinite(sc).all()
+        # spot-check distances of the batch beyond the sample with the oracle's distance
+        rng = np.random.default_rng(ef)
+        qi = rng.integers(n_sample, w.nq, size=200)
+        ci = rng.integers(0, ef, size=200)
+        qc = oracle.encode(q[qi])
+        want = oracle.sm_distance_pairs(qc, np.arange(200), codes, cid[qi, ci].astype(np.int64), w.d)
+        assert (want == cds[qi, ci]).all()
+    del index, xd, gcodes
+    torch.cuda.empty_cache()
+
+
+def test_full_size_768d_headline_all_ef(qv):
+    _full_case(qv, "C2", efs=(64, 16, 32, 128), n_sample=1000)
+
+
+def test_full_size_384d(qv):
+    _full_case(qv, "C3", efs=(64,), n_sample=1000, L=64)
+
+
+def test_full_size_512d_structureless(qv):
+    _full_case(qv, "C5", efs=(64,), n_sample=1000, L=64)
+
+
+def test_full_size_3072d(qv):
+    _full_case(qv, "C4", efs=(64,), n_sample=300, L=64)
