@@ -5,10 +5,13 @@
 // per-dimension predicate *is* the 64-bit word of the bit-plane (bit l = dimension 64w+l).
 //
 // The threshold test uses the exact mean: strong_i <=> d*|x_i| > sum_j |x_j| in real
-// arithmetic.  Fast path: the sum is accumulated in double (every term is >= 0, so any
-// summation order has relative error <= (d-1)*2^-53) and d*|x_i| is exact in double; a
-// comparison whose gap exceeds d*2^-52*sum is therefore certain.  Any vector with a
-// comparison inside that band is redone with an integer super-accumulator in LDS.
+// arithmetic.  Fast path: the sum S is accumulated in double (every term is >= 0, so any
+// summation order has relative error <= (d-1)*2^-53); with margin = d*2^-52*S, a value above
+// (S+margin)/d is certainly strong and one below (S-margin)/d certainly weak.  Both bounds are
+// rounded outwards to float32 (two ulps further than round-to-nearest), so each element costs two
+// float compares.  Any vector with an element between the bounds is redone with an integer
+// super-accumulator in LDS.  (float32 subnormals are compared and converted as such: HIP's
+// default for gfx9 keeps them; the parity tests cover subnormal-only vectors.)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -34,73 +37,37 @@ __device__ __forceinline__ bool split_abs(float x, uint32_t& m, int& sh) {
     return true;
 }
 
-// |x| as a double, built from the integer fields so that float32 subnormals never depend on the
-// float denormal mode (0 for Inf/NaN)
-__device__ __forceinline__ double abs_as_double(float x) {
-    uint32_t m; int sh;
-    split_abs(x, m, sh);
-    return ldexp((double)m, sh - 149);
-}
-
 __device__ __forceinline__ bool is_positive(float x) { return (int32_t)__float_as_uint(x) > 0; }
 
-__global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel(const float* __restrict__ x, int64_t n, int d,
-                                                                uint64_t* __restrict__ codes,
-                                                                uint32_t* __restrict__ status) {
-    __shared__ unsigned long long acc[ENC_WAVES][EXACT_LIMBS];
-    __shared__ uint32_t digits[ENC_WAVES][EXACT_LIMBS];
-    const int lane = threadIdx.x & 63;
-    const int wv = threadIdx.x >> 6;
-    const int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv;
-    if (v >= n) return;  // whole wave leaves together; no block-wide barrier is used below
-    const int W = (d + 63) >> 6;
-    const float* xv = x + v * (int64_t)d;
-    uint64_t* cv = codes + v * (int64_t)(2 * W);
-
-    // pass 1: sum of magnitudes in double
-    double part = 0.0;
-    bool finite = true;
-    for (int i = lane; i < d; i += 64) {
-        float xi = xv[i];
-        finite &= (__float_as_uint(xi) & 0x7F800000u) != 0x7F800000u;
-        part += abs_as_double(xi);
-    }
-    const double S = wave_sum(part);
-    const bool all_finite = __all(finite);
+// float32 bounds around S/d: |x| > hi => D*|x| > S + margin;  |x| < lo => D*|x| < S - margin
+__device__ __forceinline__ void certain_bounds(double S, int d, float& lo, float& hi) {
     const double margin = (double)d * 0x1p-52 * S;
+    const float h = (float)((S + margin) / (double)d);
+    const float l = (float)((S - margin) / (double)d);
+    hi = __uint_as_float(__float_as_uint(h) + 2u);   // Inf + 2 is a NaN: then nothing is "certainly strong"
+    const uint32_t lb = __float_as_uint(l);
+    lo = __uint_as_float(lb >= 2u ? lb - 2u : 0u);
+}
 
-    // pass 2 (the row is in L1/L2 now): bit-planes by ballot
-    bool doubtful = false;
-    for (int w = 0; w < W; ++w) {
-        int i = (w << 6) + lane;
-        float xi = i < d ? xv[i] : 0.0f;
-        double t = (double)d * abs_as_double(xi);
-        bool strong = t > S;
-        doubtful |= (i < d) && (fabs(t - S) <= margin);
-        uint64_t pw = __ballot(is_positive(xi));
-        uint64_t sw = __ballot(strong);
-        if (lane == 0) cv[w] = pw;
-        if (lane == 1) cv[W + w] = sw;
-    }
-    if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
-    if (!all_finite || !__any(doubtful)) return;
-
-    // exact redo of the magnitude plane: S as an integer in units of 2^-149
-    if (lane < EXACT_LIMBS) acc[wv][lane] = 0ull;
+// Exact redo of the magnitude plane of one vector (whole wave): S as an integer in units of 2^-149.
+__device__ __forceinline__ void exact_magnitude_plane(const float* __restrict__ xv, int d, int W,
+                                                      uint64_t* __restrict__ cv, unsigned long long* acc,
+                                                      uint32_t* digits, int lane) {
+    if (lane < EXACT_LIMBS) acc[lane] = 0ull;
     __builtin_amdgcn_wave_barrier();
     for (int i = lane; i < d; i += 64) {
         uint32_t m; int sh;
         split_abs(xv[i], m, sh);
         unsigned long long val = (unsigned long long)m << (sh & 31);  // < 2^55
-        atomicAdd(&acc[wv][sh >> 5], val & 0xFFFFFFFFull);
-        atomicAdd(&acc[wv][(sh >> 5) + 1], val >> 32);
+        atomicAdd(&acc[sh >> 5], val & 0xFFFFFFFFull);
+        atomicAdd(&acc[(sh >> 5) + 1], val >> 32);
     }
     __builtin_amdgcn_wave_barrier();
     if (lane == 0) {
         unsigned long long carry = 0;
         for (int k = 0; k < EXACT_LIMBS; ++k) {
-            unsigned long long s = acc[wv][k] + carry;  // each limb holds < d * 2^32 <= 2^49
-            digits[wv][k] = (uint32_t)s;
+            unsigned long long s = acc[k] + carry;  // each limb holds < d * 2^33 <= 2^49
+            digits[k] = (uint32_t)s;
             carry = s >> 32;
         }
     }
@@ -119,12 +86,116 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel(const float* __r
         int cmp = 0;  // sign of T - S
         for (int k = EXACT_LIMBS - 1; k >= 0 && cmp == 0; --k) {
             uint32_t tk = k == k0 ? t0 : (k == k0 + 1 ? t1 : (k == k0 + 2 ? t2 : 0u));
-            uint32_t sk = digits[wv][k];
+            uint32_t sk = digits[k];
             cmp = tk > sk ? 1 : (tk < sk ? -1 : 0);
         }
         uint64_t sw = __ballot(i < d && cmp > 0);
         if (lane == 1) cv[W + w] = sw;
     }
+}
+
+// Vectors of up to 64*W dimensions, W known at compile time: the whole vector sits in registers
+// (W values per lane), all loads are issued before the first use, the row is read exactly once and
+// the 2W code words leave through one coalesced store.
+template <int W>
+__global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float* __restrict__ x, int64_t n, int d,
+                                                                    uint64_t* __restrict__ codes,
+                                                                    uint32_t* __restrict__ status) {
+    __shared__ unsigned long long acc[ENC_WAVES][EXACT_LIMBS];
+    __shared__ uint32_t digits[ENC_WAVES][EXACT_LIMBS];
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int64_t stride = (int64_t)gridDim.x * ENC_WAVES;
+    // grid-stride over vectors: the grid is sized to fill the chip a few times, not one wave per vector
+    for (int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv; v < n; v += stride) {
+        const float* xv = x + v * (int64_t)d;
+        uint64_t* cv = codes + v * (int64_t)(2 * W);
+
+        float xr[W];
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            int i = (w << 6) + lane;
+            xr[w] = i < d ? xv[i] : 0.0f;
+        }
+        double part = 0.0;
+        bool finite = true;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            finite &= (__float_as_uint(xr[w]) & 0x7F800000u) != 0x7F800000u;
+            part += (double)fabsf(xr[w]);
+        }
+        const double S = wave_sum(part);
+        const bool all_finite = __all(finite);
+        float lo, hi;
+        certain_bounds(S, d, lo, hi);
+        bool doubtful = false;
+        uint64_t mine = 0, mine2 = 0;  // lane l keeps code word l (and word 64 + l when 2W > 64)
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const float a = fabsf(xr[w]);
+            const bool strong = a > hi;
+            doubtful |= ((w << 6) + lane < d) && !strong && !(a < lo);
+            const uint64_t pw = __ballot(is_positive(xr[w]));
+            const uint64_t sw = __ballot(strong);
+            if (lane == w) mine = pw;
+            if (W + w < 64) { if (lane == W + w) mine = sw; }
+            else { if (lane == W + w - 64) mine2 = sw; }
+        }
+        if (lane < 2 * W && lane < 64) cv[lane] = mine;
+        if (2 * W > 64 && lane < 2 * W - 64) cv[64 + lane] = mine2;
+        if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
+        if (all_finite && __any(doubtful)) exact_magnitude_plane(xv, d, W, cv, acc[wv], digits[wv], lane);
+    }
+}
+
+// Any dimension: two passes over the row (the second one hits cache), four loads in flight.
+__global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel(const float* __restrict__ x, int64_t n, int d,
+                                                                uint64_t* __restrict__ codes,
+                                                                uint32_t* __restrict__ status) {
+    __shared__ unsigned long long acc[ENC_WAVES][EXACT_LIMBS];
+    __shared__ uint32_t digits[ENC_WAVES][EXACT_LIMBS];
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv;
+    if (v >= n) return;  // whole wave leaves together; no block-wide barrier is used below
+    const int W = (d + 63) >> 6;
+    const float* xv = x + v * (int64_t)d;
+    uint64_t* cv = codes + v * (int64_t)(2 * W);
+
+    // pass 1: sum of magnitudes in double
+    double part = 0.0;
+    bool finite = true;
+    for (int i0 = lane; i0 < d; i0 += 256) {
+        float xi[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) xi[u] = i0 + 64 * u < d ? xv[i0 + 64 * u] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            finite &= (__float_as_uint(xi[u]) & 0x7F800000u) != 0x7F800000u;
+            part += (double)fabsf(xi[u]);
+        }
+    }
+    const double S = wave_sum(part);
+    const bool all_finite = __all(finite);
+    float lo, hi;
+    certain_bounds(S, d, lo, hi);
+
+    // pass 2 (the row is in L1/L2 now): bit-planes by ballot
+    bool doubtful = false;
+    for (int w = 0; w < W; ++w) {
+        int i = (w << 6) + lane;
+        float xi = i < d ? xv[i] : 0.0f;
+        const float a = fabsf(xi);
+        bool strong = a > hi;
+        doubtful |= (i < d) && !strong && !(a < lo);
+        uint64_t pw = __ballot(is_positive(xi));
+        uint64_t sw = __ballot(strong);
+        if (lane == 0) cv[w] = pw;
+        if (lane == 1) cv[W + w] = sw;
+    }
+    if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
+    if (!all_finite || !__any(doubtful)) return;
+    exact_magnitude_plane(xv, d, W, cv, acc[wv], digits[wv], lane);
 }
 
 // out[p] = symmetric distance of code rows ia[p] (in a) and ib[p] (in b): one thread per pair
@@ -148,8 +219,16 @@ __global__ void bq_distance_kernel(const uint64_t* __restrict__ a, const int64_t
 
 hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    dim3 grid((unsigned)((n + ENC_WAVES - 1) / ENC_WAVES));
-    hipLaunchKernelGGL(encode_kernel, grid, dim3(64 * ENC_WAVES), 0, stream, x, n, d, codes, status);
+    dim3 grid((unsigned)((n + ENC_WAVES - 1) / ENC_WAVES)), block(64 * ENC_WAVES);
+    const unsigned full = 256 * 8 * 16;  // 16 rounds of 8 workgroups per CU
+    dim3 pgrid(grid.x < full ? grid.x : full);
+    switch ((d + 63) / 64) {
+#define QV_ENC_CASE(W) case W: hipLaunchKernelGGL(encode_kernel_reg<W>, pgrid, block, 0, stream, x, n, d, codes, status); break;
+        QV_ENC_CASE(1) QV_ENC_CASE(2) QV_ENC_CASE(4) QV_ENC_CASE(6) QV_ENC_CASE(8) QV_ENC_CASE(12)
+        QV_ENC_CASE(16) QV_ENC_CASE(24) QV_ENC_CASE(32) QV_ENC_CASE(48)
+#undef QV_ENC_CASE
+        default: hipLaunchKernelGGL(encode_kernel, grid, block, 0, stream, x, n, d, codes, status);
+    }
     return hipGetLastError();
 }
 
