@@ -57,7 +57,7 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
     ap.add_argument("--nq", type=int, default=0)
     ap.add_argument("--ef", type=int, default=64)
-    ap.add_argument("--hash-bits", type=int, default=0)
+    ap.add_argument("--visited-slots", type=int, default=0)
     ap.add_argument("--lanes-per-row", type=int, default=0)
     ap.add_argument("--table-format", type=int, default=0)
     ap.add_argument("--calib-copy", action="store_true",
@@ -105,8 +105,8 @@ def main() -> int:
     log(f"encode base: {enc_ms:.3f} ms, {enc_bytes / enc_ms / 1e6:.0f} GB/s")
 
     index = qv.Index(adjd, codes, xd, entry)
-    if args.hash_bits or args.lanes_per_row or args.table_format:
-        index.set_tuning(args.hash_bits, args.lanes_per_row, args.table_format)
+    if args.visited_slots or args.lanes_per_row or args.table_format:
+        index.set_tuning(args.visited_slots, args.lanes_per_row, args.table_format)
     ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
 
     # one traced pass: counters for the algorithmic-byte model, results for recall / parity

@@ -128,11 +128,12 @@ void qv_index_set_timer(qv_index* index, qv_timer* t /* NULL detaches */);
 int qv_timer_read(qv_timer* t, float* ms, int max_calls);
 
 /* Tunables of the search kernel (defaults picked from the shape when 0).  Host only.
- *    hash_bits       log2 of the per-query visited-table slots (10..15)
+ *    visited_slots   slots of the per-query visited table, 1024..28672 (rounded up to a multiple of 1024; to a
+ *                    power of two and at most 8192 with 32-bit entries)
  *    lanes_per_row   lanes that share one neighbour's code during the gather (1, 2, 4, 8 or 16)
  *    table_format    0: 16-bit visited-table entries whenever the graph is small enough for them
  *                    (about 4M nodes at 8192 slots), else 32-bit; 32: always 32-bit entries */
-int qv_index_set_tuning(qv_index* index, int hash_bits, int lanes_per_row, int table_format);
+int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format);
 
 const char* qv_strerror(int code);
 const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */

@@ -192,8 +192,8 @@ class Index:
         self._h = h
         self._timer = None
 
-    def set_tuning(self, hash_bits: int = 0, lanes_per_row: int = 0, table_format: int = 0) -> None:
-        _check(_lib.qv_index_set_tuning(self._h, hash_bits, lanes_per_row, table_format), "qv_index_set_tuning")
+    def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0) -> None:
+        _check(_lib.qv_index_set_tuning(self._h, visited_slots, lanes_per_row, table_format), "qv_index_set_tuning")
 
     def set_timer(self, timer: Timer | None) -> None:
         self._timer = timer

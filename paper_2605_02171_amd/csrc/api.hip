@@ -55,7 +55,7 @@ struct qv_index {
     const uint64_t* codes;
     const float* vecs;
     uint32_t entry;
-    int hash_bits;      // <= 0: choose from ef
+    int visited_slots;  // <= 0: choose from ef
     int lanes_per_row;  // <= 0: choose from d
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
     qv_timer* timer;
@@ -94,20 +94,19 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->hash_bits = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->timer = nullptr;
     *out = ix;
     return QV_OK;
 }
 
 void qv_index_free(qv_index* index) { delete index; }
 
-int qv_index_set_tuning(qv_index* index, int hash_bits, int lanes_per_row, int table_format) {
+int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format) {
     if (!index) return QV_ERR_NULL;
-    if (hash_bits > 0 && (hash_bits < 10 || hash_bits > 15)) return QV_ERR_INVALID_ARG;
+    if (visited_slots != 0 && (visited_slots < 1024 || visited_slots > 28672)) return QV_ERR_INVALID_ARG;
     if (table_format != 0 && table_format != 32) return QV_ERR_INVALID_ARG;
-    if (hash_bits == 15 && table_format == 32) return QV_ERR_INVALID_ARG;  // 128 KB would not fit
     if (lanes_per_row > 0 && (lanes_per_row > 16 || (lanes_per_row & (lanes_per_row - 1)))) return QV_ERR_INVALID_ARG;
-    index->hash_bits = hash_bits;
+    index->visited_slots = visited_slots;
     index->lanes_per_row = lanes_per_row;
     index->table_format = table_format;
     return QV_OK;
@@ -147,10 +146,12 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes;
     sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
-    if (index->hash_bits > 0) sp.hash_bits = index->hash_bits;
-    else sp.hash_bits = ef <= 16 ? 12 : (ef <= 64 ? 13 : (ef <= 128 ? 14 : 15));
-    qv::plan_visited_table(sp, index->table_format != 32);
-    if (sp.vis_regions == 0 && index->hash_bits <= 0 && sp.hash_bits > 14) sp.hash_bits = 14;  // 64 KB of LDS
+    // default table: about two slots per expected distance evaluation (~45 per unit of ef at degree 64)
+    int slots = index->visited_slots > 0 ? index->visited_slots : (ef <= 16 ? 4096 : (ef <= 64 ? 8192 : (ef <= 128 ? 16384 : 28672)));
+    qv::plan_visited_table(sp, (uint32_t)slots, index->table_format != 32);
+    if (sp.vis_regions == 0 && sp.vis_slots > 8192) {  // 32-bit entries: keep the table within 32 KB of LDS
+        qv::plan_visited_table(sp, 8192, false);
+    }
     // the final lists go straight into the caller's trace buffers when there are any
     sp.cand_ids = trace && trace->cand_ids ? trace->cand_ids : reinterpret_cast<uint32_t*>(ws + L.cand_ids);
     sp.cand_dist = trace && trace->cand_dist ? trace->cand_dist : reinterpret_cast<uint32_t*>(ws + L.cand_dist);

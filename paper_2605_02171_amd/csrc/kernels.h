@@ -20,7 +20,8 @@ struct SearchParams {
     int R;
     uint32_t entry;
     int ef;
-    int hash_bits;           // log2(slots) of the visited table
+    uint32_t vis_slots;      // slots of the visited table (see plan_visited_table)
+    int vis_bucket_bits;     // 32-bit entries: log2(number of 4-slot buckets)
     uint32_t vis_regions;    // > 0: 16-bit entries, table cut into this many parts ...
     uint32_t vis_region_buckets;  // ... of this many 8-tag buckets each (see plan_visited_table)
     // outputs
@@ -52,8 +53,8 @@ hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64
                               int64_t npairs, int d, uint32_t* out, hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
-size_t beam_search_lds_bytes(int nw, int hash_bits, bool narrow, int ef);
-void plan_visited_table(SearchParams& p, bool allow_narrow);
+size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef);
+void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow);
 hipError_t launch_rerank(const RerankParams& p, hipStream_t stream);
 
 }  // namespace qv

@@ -49,6 +49,19 @@ __device__ __forceinline__ uint32_t quad_xor2(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // quad_perm:[2,3,0,1]
 }
 
+// Per 64 dimensions (Table 1 of the paper as three popcounts): with X = differing signs,
+// c1 += pc(X), c2 += pc(X and (s_v or s_q)), c3 += pc(X and s_v and s_q); distance = c1 + c2 + 2*c3.
+// The two masked terms are single three-input bit operations on gfx950 (truth tables 0xE0 = a&(b|c),
+// 0x80 = a&b&c with a = 0xF0, b = 0xCC, c = 0xAA).
+__device__ __forceinline__ void sm_accumulate(uint64_t pv, uint64_t sv, uint64_t pq, uint64_t sq, uint32_t& c1,
+                                              uint32_t& c2, uint32_t& c3) {
+    const uint32_t xl = (uint32_t)pv ^ (uint32_t)pq, xh = (uint32_t)(pv >> 32) ^ (uint32_t)(pq >> 32);
+    const uint32_t svl = (uint32_t)sv, svh = (uint32_t)(sv >> 32), sql = (uint32_t)sq, sqh = (uint32_t)(sq >> 32);
+    c1 += __popc(xl) + __popc(xh);
+    c2 += __popc(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0xE0)) + __popc(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0xE0));
+    c3 += __popc(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0x80)) + __popc(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0x80));
+}
+
 // ---------------------------------------------------------------------------------------------
 // Visited set, 32-bit entries: buckets of four ids; an id lives in the first bucket, counting from
 // its home bucket, that had a free slot when it arrived.  Slots are never freed, so a lookup may
@@ -193,13 +206,12 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
     const int NW = NW_T > 0 ? NW_T : p.nw;
-    const int hbits = p.hash_bits;
-    const uint32_t cap = 1u << hbits;   // slots (32-bit each, or 16-bit when NARROW)
+    const uint32_t cap = p.vis_slots;   // slots (32-bit each, or 16-bit when NARROW)
     const uint32_t vis_regions = p.vis_regions, vis_B = p.vis_region_buckets;
     const uint32_t vis_used = NARROW ? vis_regions * vis_B * 8 : cap;
     const uint32_t vis_limit = vis_used - (vis_used >> 2) - 64;  // stop inserting at 3/4 full
     const uint32_t tab_words = NARROW ? cap >> 1 : cap;
-    const int bucket_bits = hbits - 2;
+    const int bucket_bits = p.vis_bucket_bits;
     const uint32_t bucket_mask = (1u << bucket_bits) - 1;
     uint32_t* tab = smem;
     uint32_t* list = tab + tab_words;  // [64] compacted new neighbour ids
@@ -273,10 +285,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                 if (b * RPP < m) {  // wave-uniform
 #pragma unroll
                     for (int i = 0; i < KW; ++i) {
-                        uint64_t X = pv[b][i] ^ qp[i];
-                        c1 += __popcll(X);
-                        c2 += __popcll(X & (sv[b][i] | qs[i]));
-                        c3 += __popcll(X & sv[b][i] & qs[i]);
+                        sm_accumulate(pv[b][i], sv[b][i], qp[i], qs[i], c1, c2, c3);
                     }
                 }
                 part[b] = c1 + c2 + 2u * c3;
@@ -324,10 +333,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                             uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
                             for (int i = 0; i < KW; ++i) {
-                                uint64_t X = pv[b][i] ^ qp[i];
-                                c1 += __popcll(X);
-                                c2 += __popcll(X & (sv[b][i] | qs[i]));
-                                c3 += __popcll(X & sv[b][i] & qs[i]);
+                                sm_accumulate(pv[b][i], sv[b][i], qp[i], qs[i], c1, c2, c3);
                             }
                             uint32_t dist = c1 + c2 + 2u * c3;
 #pragma unroll
@@ -343,11 +349,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     if (ri < m) {
                         const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW);
                         for (int w = sub; w < NW; w += G) {
-                            uint64_t X = row[w] ^ qlds[w];
-                            uint64_t sv = row[NW + w], sq = qlds[NW + w];
-                            c1 += __popcll(X);
-                            c2 += __popcll(X & (sv | sq));
-                            c3 += __popcll(X & sv & sq);
+                            sm_accumulate(row[w], row[NW + w], qlds[w], qlds[NW + w], c1, c2, c3);
                         }
                     }
                     uint32_t dist = c1 + c2 + 2u * c3;
@@ -469,14 +471,14 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     }
 }
 
-size_t beam_search_lds_bytes(int nw, int hash_bits, bool narrow, int ef) {
+size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef) {
     const int P = (ef + 63) / 64 <= 1 ? 1 : ((ef + 63) / 64 <= 2 ? 2 : ((ef + 63) / 64 <= 4 ? 4 : ((ef + 63) / 64 <= 8 ? 8 : 16)));
-    return ((size_t)1 << hash_bits) * (narrow ? 2 : 4) + 64 * 4 * 2 + (size_t)(64 * P + 64) * 8 + (size_t)nw * 16 + 16;
+    return (size_t)vis_slots * (narrow ? 2 : 4) + 64 * 4 * 2 + (size_t)(64 * P + 64) * 8 + (size_t)nw * 16 + 16;
 }
 
 template <int NW_T, int G, int P, bool NARROW>
 static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
-    size_t lds = beam_search_lds_bytes(p.nw, p.hash_bits, NARROW, p.ef);
+    size_t lds = beam_search_lds_bytes(p.nw, p.vis_slots, NARROW, p.ef);
     auto kern = beam_search_kernel<NW_T, G, P, NARROW>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -521,16 +523,25 @@ static int default_lanes_per_row(int nw) {
     return 16;
 }
 
-// Picks the visited-table format: 16-bit entries when every part of the table keeps >= 16 buckets.
-void plan_visited_table(SearchParams& p, bool allow_narrow) {
+// Picks the visited-table format for `slots` requested slots: 16-bit entries (slots a multiple of
+// 1024) when every part of the table keeps >= 16 buckets, else 32-bit entries (slots rounded up to a
+// power of two).
+void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow) {
     const uint32_t regions = (uint32_t)((p.n + 65534) / 65535);
-    const uint32_t buckets = (1u << p.hash_bits) / 8;
-    if (allow_narrow && buckets / regions >= 16) {
+    slots = (slots + 1023u) & ~1023u;
+    if (allow_narrow && slots / 8 / regions >= 16) {
+        p.vis_slots = slots;
         p.vis_regions = regions;
-        p.vis_region_buckets = buckets / regions;
+        p.vis_region_buckets = slots / 8 / regions;
+        p.vis_bucket_bits = 0;
     } else {
+        uint32_t pow2 = 1024;
+        while (pow2 < slots) pow2 <<= 1;
+        p.vis_slots = pow2;
         p.vis_regions = 0;
         p.vis_region_buckets = 0;
+        p.vis_bucket_bits = 0;
+        while ((4u << p.vis_bucket_bits) < pow2) p.vis_bucket_bits++;
     }
 }
 

@@ -90,15 +90,15 @@ def test_bq_distance_bit_exact(qv, d):
     assert (qv.to_numpy_u32(same) == 0).all()
 
 
-def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, hash_bits=0, lanes=0, table_format=0):
+def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, visited_slots=0, lanes=0, table_format=0):
     codes = oracle.encode(x, threads=8)
     ref = oracle.search(q, adj, codes, x, entry, k, ef, visit_cap=visit_cap, threads=8)
     xd = torch.from_numpy(x).cuda()
     gcodes = qv.encode(xd)
     assert (qv.to_numpy_u64(gcodes) == codes).all()
     index = qv.Index(qv.from_numpy_u32(adj), gcodes, xd, entry)
-    if hash_bits or lanes or table_format:
-        index.set_tuning(hash_bits, lanes, table_format)
+    if visited_slots or lanes or table_format:
+        index.set_tuning(visited_slots, lanes, table_format)
     out = qv.search(index, torch.from_numpy(q).cuda(), k, ef, trace=True, visit_cap=visit_cap)
     torch.cuda.synchronize()
     return ref, out
@@ -158,7 +158,7 @@ def test_search_full_visited_table_keeps_results_exact(qv, table_format):
     w = datagen.scaled("C2", n=20_000, nq=40)
     x, q = datagen.make_base(w), datagen.make_queries(w)
     adj, entry = graph.build_graph(x, 64, 64, 1.2)
-    ref, out = _run_both(qv, x, q, adj, entry, 10, 128, visit_cap=300, hash_bits=10, table_format=table_format)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, 128, visit_cap=300, visited_slots=1024, table_format=table_format)
     st = qv.to_numpy_u32(out.status)
     assert (st & 2).any(), "the test is meant to overflow the table"
     _assert_search_equal(qv, ref, out, exact_counters=False)
@@ -189,7 +189,7 @@ def test_search_small_table_in_eight_parts_overflows_gracefully(qv):
     x = rng.standard_normal((n, d)).astype(np.float32)
     q = rng.standard_normal((64, d)).astype(np.float32)
     adj = datagen.random_regular_graph(n, 16, seed=9)
-    ref, out = _run_both(qv, x, q, adj, entry=11, k=10, ef=128, visit_cap=300, hash_bits=10)
+    ref, out = _run_both(qv, x, q, adj, entry=11, k=10, ef=128, visit_cap=300, visited_slots=1024)
     assert (qv.to_numpy_u32(out.status) & 2).all()
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
