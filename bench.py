@@ -146,6 +146,24 @@ def main() -> int:
     log(f"{ms_per_step:.3f} ms/step, {qps:.0f} QPS; stages (ms): encode {stage_ms[:, 0].mean():.3f}, "
         f"search {search_ms:.3f}, rerank {stage_ms[:, 2].mean():.3f}")
 
+    # ceiling of the memory system for the search kernel's gather pattern: as many random code rows as the
+    # batch evaluates, no arithmetic
+    gather_gbps = None
+    n_rows = int(n_eval.sum()) // 64 * 64
+    if n_rows >= 64:
+        rid = torch.randint(0, w.n, (n_rows,), device="cuda", dtype=torch.int32)
+        qv.gather_probe(codes, w.d, rid)
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(3):
+            qv.gather_probe(codes, w.d, rid)
+        g1.record()
+        torch.cuda.synchronize()
+        gather_gbps = n_rows * (code_b + 4) / (g0.elapsed_time(g1) / 3 * 1e-3) / 1e9
+        log(f"random code-row gather ceiling: {gather_gbps:.0f} GB/s")
+        del rid
+
     if args.calib_copy:
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         b = torch.empty_like(a)
@@ -171,16 +189,24 @@ def main() -> int:
         t0 = time.time()
         ref = oracle.search(q[:ns], adj, ocodes, x, entry, k, ef, threads=threads)
         t_cpu = time.time() - t0
+        exact = (status[:ns] & 2) == 0          # queries whose visited table never filled up
         parity = bool((ref.cand_ids == qv.to_numpy_u32(traced.cand_ids)[:ns]).all() and
                       (ref.cand_dist == qv.to_numpy_u32(traced.cand_dist)[:ns]).all() and
-                      (ref.n_dist_evals == n_eval[:ns]).all() and
-                      (ocodes == qv.to_numpy_u64(codes)).all())
+                      (ref.n_expanded == n_exp[:ns]).all() and
+                      (ref.n_dist_evals[exact] == n_eval[:ns][exact]).all() and
+                      (ref.n_dist_evals <= n_eval[:ns]).all() and
+                      (ocodes == qv.to_numpy_u64(codes)).all() and
+                      np.allclose(ref.scores, traced.scores.cpu().numpy()[:ns], rtol=1e-5, atol=1e-7))
         orecall = float(np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ref.ids, gt[:ns])]) / k)
-        cpu = {"value": ns / t_cpu, "unit": "queries/s", "cores": threads, "kind": "oracle",
+        n1 = min(200, ns)
+        t0 = time.time()
+        oracle.search(q[:n1], adj, ocodes, x, entry, k, ef, threads=1)
+        t_1t = time.time() - t0
+        cpu = {"value": ns / t_cpu, "single_thread_value": n1 / t_1t, "unit": "queries/s", "cores": threads, "kind": "oracle",
                "sample": f"first {ns} of the {w.nq} queries, same graph/codes/vectors; search+rerank wall time "
                          f"{t_cpu:.2f}s ({threads} threads); base encode by the oracle took {t_enc:.1f}s (not included)",
                "recall_at_10": orecall}
-        log(f"oracle: {ns / t_cpu:.0f} QPS on {threads} threads, recall {orecall:.4f}, parity with GPU: {parity}")
+        log(f"oracle: {n1 / t_1t:.0f} QPS on 1 thread ({n1} queries), {ns / t_cpu:.0f} QPS on {threads} threads, recall {orecall:.4f}, parity with GPU: {parity}")
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}_ef{ef}.json")
@@ -206,6 +232,9 @@ def main() -> int:
         "whole_path_GBps": (encq_bytes + search_bytes + rerank_bytes) / (ms_per_step * 1e-3) / 1e9,
         "encode_base": {"ms": enc_ms, "GBps": enc_bytes / enc_ms / 1e6},
         "graph_build_s": t_graph,
+        "random_row_gather_ceiling_GBps": gather_gbps,
+        "search_bytes_line_granular": int(4 * w.R * n_exp.sum() + (2 * 128 if code_b % 128 else code_b) * n_eval.sum())
+        if code_b <= 256 else None,
         "parity_with_oracle_on_sample": parity,
         "roofline": {"kernel": "beam_search_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},

@@ -70,6 +70,15 @@ int qv_bq_distance(const uint64_t* codes_a, const int64_t* ia, const uint64_t* c
                    int64_t npairs, int d, uint32_t* out, void* stream);
 
 /*
+ * Measurement aid (paper Sec. 4.2, "Cache friendliness": a hop touches one code of D/4 bytes): reads the
+ * code rows ids[0 .. n_ids) (device uint32, each < n -- the caller guarantees it; n_ids is used in
+ * multiples of 64) with the search kernel's gather pattern and no arithmetic, to measure the rate the
+ * memory system sustains for that pattern.  sink: device uint64[1], scratch.
+ */
+int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
+                    void* stream);
+
+/*
  * 2. Load (paper Sec. 4.2: hot data = codes + flat adjacency, cold data = float32 vectors).
  *    Creates a host-side handle that remembers the borrowed device buffers; copies nothing.
  *    adj    device, [n][R] uint32, QV_EMPTY = empty slot (rows need not be packed to the left)

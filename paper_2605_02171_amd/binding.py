@@ -46,6 +46,8 @@ _lib.qv_encode.restype = ctypes.c_int
 _lib.qv_encode.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, _P, _P]
 _lib.qv_bq_distance.restype = ctypes.c_int
 _lib.qv_bq_distance.argtypes = [_P, _P, _P, _P, ctypes.c_int64, ctypes.c_int, _P, _P]
+_lib.qv_gather_probe.restype = ctypes.c_int
+_lib.qv_gather_probe.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, ctypes.c_int64, _P, _P]
 _lib.qv_index_load.restype = ctypes.c_int
 _lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P,
                                ctypes.c_uint32]
@@ -149,6 +151,15 @@ def bq_distance(codes_a: torch.Tensor, ia: torch.Tensor, codes_b: torch.Tensor, 
     _check(_lib.qv_bq_distance(codes_a.data_ptr(), ia.data_ptr(), codes_b.data_ptr(), ib.data_ptr(), ia.numel(),
                                int(d), out.data_ptr(), _stream()), "qv_bq_distance")
     return out
+
+
+def gather_probe(codes: torch.Tensor, d: int, ids: torch.Tensor) -> None:
+    """qv_gather_probe: read the code rows named by ids (int32 holding uint32, all < n) and discard them."""
+    codes = _dev(codes, torch.int64, "codes")
+    ids = _dev(ids, torch.int32, "ids")
+    sink = torch.zeros(1, dtype=torch.int64, device=codes.device)
+    _check(_lib.qv_gather_probe(codes.data_ptr(), codes.shape[0], int(d), ids.data_ptr(), ids.numel(),
+                                sink.data_ptr(), _stream()), "qv_gather_probe")
 
 
 class Timer:

@@ -84,6 +84,15 @@ int qv_bq_distance(const uint64_t* codes_a, const int64_t* ia, const uint64_t* c
     return e == hipSuccess ? QV_OK : hip_fail(e, "bq_distance launch");
 }
 
+int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
+                    void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (n < 1 || n_ids < 0) return QV_ERR_INVALID_ARG;
+    if (!codes || !ids || !sink) return QV_ERR_NULL;
+    hipError_t e = qv::launch_gather_probe(codes, d, ids, n_ids, sink, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "gather probe launch");
+}
+
 int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, const uint64_t* codes,
                   const float* vecs, uint32_t entry) {
     if (!out) return QV_ERR_NULL;
@@ -147,7 +156,12 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes;
     sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
     // default table: about two slots per expected distance evaluation (~45 per unit of ef at degree 64)
-    int slots = index->visited_slots > 0 ? index->visited_slots : (ef <= 16 ? 4096 : (ef <= 64 ? 8192 : (ef <= 128 ? 16384 : 28672)));
+    int slots = index->visited_slots > 0 ? index->visited_slots : 96 * ef + 2048;
+    // everything a query keeps in LDS has to fit 64 KB
+    const size_t fixed = qv::beam_search_lds_bytes(sp.nw, 0, true, ef);
+    const int max_narrow = (int)((65536 - fixed) / 2 / 1024 * 1024);
+    if (slots > max_narrow) slots = max_narrow;
+    if (slots < 1024) slots = 1024;
     qv::plan_visited_table(sp, (uint32_t)slots, index->table_format != 32);
     if (sp.vis_regions == 0 && sp.vis_slots > 8192) {  // 32-bit entries: keep the table within 32 KB of LDS
         qv::plan_visited_table(sp, 8192, false);

@@ -217,6 +217,44 @@ __global__ void bq_distance_kernel(const uint64_t* __restrict__ a, const int64_t
     out[p] = c1 + c2 + 2u * c3;
 }
 
+// Measurement aid: every wave reads 64 rows of 2W words per round, rows named by ids[], with the access
+// pattern of the search kernel's code gather (4 lanes per row, 8-byte loads) and no arithmetic beyond an
+// XOR fold, so its rate is what the memory system gives to that pattern.
+__global__ __launch_bounds__(64) void gather_probe_kernel(const uint64_t* __restrict__ codes, int row_words,
+                                                          const uint32_t* __restrict__ ids, int64_t n_ids,
+                                                          uint64_t* __restrict__ sink) {
+    const int lane = threadIdx.x, sub = lane & 3, grp = lane >> 2;
+    uint64_t acc = 0;
+    for (int64_t base = (int64_t)blockIdx.x * 64; base + 64 <= n_ids; base += (int64_t)gridDim.x * 64) {
+        const uint32_t mine = ids[base + lane];
+        for (int w0 = sub; w0 < row_words; w0 += 24) {
+            uint64_t t[4][6];  // up to 24 loads in flight per lane, as in the search kernel
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t row = (uint32_t)__shfl((int)mine, b * 16 + grp);
+                const uint64_t* p = codes + (int64_t)row * row_words;
+#pragma unroll
+                for (int u = 0; u < 6; ++u) t[b][u] = w0 + 4 * u < row_words ? p[w0 + 4 * u] : 0ull;
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int u = 0; u < 6; ++u) acc ^= t[b][u];
+        }
+    }
+    if (acc == 0x0123456789ABCDEFull) sink[0] = acc;  // keeps the loads alive
+}
+
+hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
+                               hipStream_t stream) {
+    if (n_ids < 64) return hipSuccess;
+    int64_t blocks = n_ids / 64;
+    if (blocks > 256 * 40) blocks = 256 * 40;
+    hipLaunchKernelGGL(gather_probe_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, codes, 2 * ((d + 63) / 64), ids,
+                       n_ids, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, hipStream_t stream) {
     if (n == 0) return hipSuccess;
     dim3 grid((unsigned)((n + ENC_WAVES - 1) / ENC_WAVES)), block(64 * ENC_WAVES);

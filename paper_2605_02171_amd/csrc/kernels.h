@@ -51,6 +51,8 @@ struct RerankParams {
 hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, hipStream_t stream);
 hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
                               int64_t npairs, int d, uint32_t* out, hipStream_t stream);
+hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
+                               hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
 size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef);

@@ -194,6 +194,16 @@ def test_search_small_table_in_eight_parts_overflows_gracefully(qv):
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
+@pytest.mark.parametrize("ef", [256, 512, 1024])
+def test_search_wide_beams(qv, ef):
+    # beams beyond two registers per lane; at ef = 1024 the visited table is capped by the 64 KB of LDS
+    w = datagen.scaled("C2", n=40_000, nq=24)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 48, 1.2)
+    ref, out = _run_both(qv, x, q, adj, entry, 10, ef, visit_cap=1200)
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
 def test_search_degenerate_graphs(qv):
     rng = np.random.default_rng(3)
     n, d = 500, 96
