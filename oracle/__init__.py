@@ -55,6 +55,12 @@ def _load():
         lib.orc_search.argtypes = [P, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, P, P, P,
                                    ctypes.c_uint32, ctypes.c_int, ctypes.c_int, P, P, P, P, P, P,
                                    ctypes.c_int64, ctypes.c_int]
+        lib.orc_bq_scan.restype = ctypes.c_int
+        lib.orc_bq_scan.argtypes = [P, ctypes.c_int64, ctypes.c_int, P, ctypes.c_int64, ctypes.c_int, P, P, ctypes.c_int]
+        lib.orc_cosine_topk.restype = ctypes.c_int
+        lib.orc_cosine_topk.argtypes = [P, ctypes.c_int64, ctypes.c_int, P, ctypes.c_int64, ctypes.c_int, P, ctypes.c_int]
+        lib.orc_topk_overlap.restype = ctypes.c_double
+        lib.orc_topk_overlap.argtypes = [P, P, ctypes.c_int64, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -170,3 +176,34 @@ def rerank(queries, vecs, cand_ids, n_cand, k: int):
     _check(_load().orc_rerank(_ptr(queries), nq, d, _ptr(vecs), _ptr(cand_ids), ef, _ptr(n_cand), int(k),
                               _ptr(ids), _ptr(scores), _ptr(all_scores)), "orc_rerank")
     return ids, scores, all_scores
+
+
+def bq_scan(codes, qcodes, d: int, K: int, threads: int = 1):
+    """Brute force in code space: (ids [nq,K], dist [nq,K]) of the K smallest (distance, id) per query code."""
+    codes = _c(codes, np.uint64)
+    qcodes = _c(qcodes, np.uint64)
+    assert codes.shape[1] == code_words(d) and qcodes.shape[1] == code_words(d)
+    nq = qcodes.shape[0]
+    ids = np.zeros((nq, K), dtype=np.uint32)
+    dist = np.zeros((nq, K), dtype=np.uint32)
+    _check(_load().orc_bq_scan(_ptr(codes), codes.shape[0], int(d), _ptr(qcodes), nq, int(K), _ptr(ids), _ptr(dist),
+                               int(threads)), "orc_bq_scan")
+    return ids, dist
+
+
+def cosine_topk(vecs, queries, K: int, threads: int = 1):
+    """Exact top-K by cosine on the float32 data (double accumulation) -> ids [nq,K]."""
+    vecs = _c(vecs, np.float32)
+    queries = _c(queries, np.float32)
+    nq, d = queries.shape
+    ids = np.zeros((nq, K), dtype=np.uint32)
+    _check(_load().orc_cosine_topk(_ptr(vecs), vecs.shape[0], d, _ptr(queries), nq, int(K), _ptr(ids), int(threads)),
+           "orc_cosine_topk")
+    return ids
+
+
+def topk_overlap(a, b) -> float:
+    a = _c(a, np.uint32)
+    b = _c(b, np.uint32)
+    assert a.shape == b.shape
+    return float(_load().orc_topk_overlap(_ptr(a), _ptr(b), a.shape[0], a.shape[1]))

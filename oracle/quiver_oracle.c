@@ -390,3 +390,85 @@ int orc_search(const float *queries, int64_t nq, int64_t n, int d, int R, const 
     }
     return rc;
 }
+
+/* ------------------------------------------------------------------ */
+/* Brute-force scan in code space (Sec. 6 "Practical compatibility     */
+/* test"; Sec. 5.4 Table 10 "Top-10 overlap"): for every query code    */
+/* the K base codes with the smallest (distance, id), by computing     */
+/* every distance.  ids/dist: [nq][K], ORC_EMPTY padded when n < K.    */
+/* ------------------------------------------------------------------ */
+int orc_bq_scan(const uint64_t *codes, int64_t n, int d, const uint64_t *qcodes, int64_t nq, int K, uint32_t *ids,
+                uint32_t *dist, int threads) {
+    if (!codes || !qcodes || !ids || !dist || n < 0 || nq < 0 || d < 1 || K < 1) return ORC_ERR_ARG;
+    if (threads < 1) threads = 1;
+    int cw = orc_code_words(d);
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+    for (int64_t q = 0; q < nq; ++q) {
+        uint32_t *bi = ids + q * K, *bd = dist + q * K;
+        int size = 0;
+        for (int j = 0; j < K; ++j) bi[j] = bd[j] = ORC_EMPTY;
+        for (int64_t v = 0; v < n; ++v) {
+            uint32_t dv = orc_sm_distance(qcodes + q * cw, codes + v * cw, d);
+            if (size < K || key_less(dv, (uint32_t)v, bd[size - 1], bi[size - 1])) {
+                int p = size < K ? size : K - 1;
+                while (p > 0 && key_less(dv, (uint32_t)v, bd[p - 1], bi[p - 1])) {
+                    bd[p] = bd[p - 1];
+                    bi[p] = bi[p - 1];
+                    --p;
+                }
+                bd[p] = dv;
+                bi[p] = (uint32_t)v;
+                if (size < K) size++;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/* Exact float32-data top-K by cosine (double accumulation), order (score desc, id asc): the other side of the
+ * overlap probe.  ids: [nq][K], ORC_EMPTY padded. */
+int orc_cosine_topk(const float *vecs, int64_t n, int d, const float *queries, int64_t nq, int K, uint32_t *ids,
+                    int threads) {
+    if (!vecs || !queries || !ids || n < 0 || nq < 0 || d < 1 || K < 1) return ORC_ERR_ARG;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+    for (int64_t q = 0; q < nq; ++q) {
+        uint32_t *bi = ids + q * K;
+        float *bs = (float *)malloc(sizeof(float) * (size_t)K);
+        int size = 0;
+        for (int j = 0; j < K; ++j) bi[j] = ORC_EMPTY;
+        for (int64_t v = 0; v < n; ++v) {
+            float s = cosine(queries + q * d, vecs + v * d, d);
+            if (size < K || rank_before(s, (uint32_t)v, bs[size - 1], bi[size - 1])) {
+                int p = size < K ? size : K - 1;
+                while (p > 0 && rank_before(s, (uint32_t)v, bs[p - 1], bi[p - 1])) {
+                    bs[p] = bs[p - 1];
+                    bi[p] = bi[p - 1];
+                    --p;
+                }
+                bs[p] = s;
+                bi[p] = (uint32_t)v;
+                if (size < K) size++;
+            }
+        }
+        free(bs);
+    }
+    return ORC_OK;
+}
+
+/* Mean fraction of a[q][0..K) that also occurs in b[q][0..K) (ORC_EMPTY entries never match). */
+double orc_topk_overlap(const uint32_t *a, const uint32_t *b, int64_t nq, int K) {
+    if (!a || !b || nq < 1 || K < 1) return -1.0;
+    int64_t hits = 0;
+    for (int64_t q = 0; q < nq; ++q)
+        for (int i = 0; i < K; ++i) {
+            uint32_t x = a[q * K + i];
+            if (x == ORC_EMPTY) continue;
+            for (int j = 0; j < K; ++j)
+                if (b[q * K + j] == x) {
+                    hits++;
+                    break;
+                }
+        }
+    return (double)hits / (double)(nq * K);
+}
