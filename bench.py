@@ -60,6 +60,7 @@ def main() -> int:
     ap.add_argument("--visited-slots", type=int, default=0)
     ap.add_argument("--lanes-per-row", type=int, default=0)
     ap.add_argument("--table-format", type=int, default=0)
+    ap.add_argument("--no-scan", action="store_true", help="skip the brute-force code scan / overlap probe")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one elementwise copy kernel (1 GiB read + 1 GiB write) to calibrate byte counters")
     ap.add_argument("--cpu-sample", type=int, default=10000, help="queries the CPU oracle is timed on (0 = skip)")
@@ -176,6 +177,33 @@ def main() -> int:
     recall = float(np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(ids_gpu, gt)]) / k)
     log(f"Recall@{k} = {recall:.4f}")
 
+    # brute-force scan in code space (all queries x all base codes) and the overlap probe against exact top-10
+    scan = None
+    if not args.no_scan:
+        qcodes_d = qv.encode(qd)
+        sid, sdist = qv.bq_scan(codes, qcodes_d, w.d, k)
+        torch.cuda.synchronize()
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        sid, sdist = qv.bq_scan(codes, qcodes_d, w.d, k)
+        s1.record()
+        torch.cuda.synchronize()
+        scan_ms = s0.elapsed_time(s1)
+        hits = qv.topk_overlap(sid, torch.from_numpy(gt.astype(np.uint32).view(np.int32)).cuda())
+        overlap = float(qv.to_numpy_u32(hits).sum()) / (w.nq * k)
+        found = qv.topk_overlap(sid, qv.from_numpy_u32(np.ascontiguousarray(qv.to_numpy_u32(traced.cand_ids)[:, :k])))
+        lane_ops = 6.0 * 2 * ((w.d + 31) // 32) / 2 * w.nq * w.n   # xor, 2 three-input ops, 3 popcount-adds per 32 dims
+        alu_peak = 256 * 64 * 2.4e9
+        scan = {"ms": scan_ms, "dist_evals_per_s": w.nq * w.n / (scan_ms * 1e-3),
+                "top10_overlap_code_vs_exact": overlap,
+                "graph_search_finds_code_top10": float(qv.to_numpy_u32(found).sum()) / (w.nq * k),
+                "roofline": {"kernel": "bq_scan_kernel", "bound": "alu", "achieved": lane_ops / (scan_ms * 1e-3) / 1e12,
+                             "peak": alu_peak / 1e12, "unit": "T lane-ops/s (int32 VALU)",
+                             "frac": lane_ops / (scan_ms * 1e-3) / alu_peak}}
+        log(f"code scan {w.nq} x {w.n}: {scan_ms:.1f} ms, {scan['dist_evals_per_s'] / 1e9:.1f} G dist/s, "
+            f"{scan['roofline']['frac']:.2f} of VALU peak; top-10 overlap code vs exact {overlap:.3f}; "
+            f"beam search finds {scan['graph_search_finds_code_top10']:.3f} of the code-space top-10")
+
     # CPU oracle on a bounded sample of the same queries, all host threads
     cpu = None
     parity = None
@@ -239,6 +267,7 @@ def main() -> int:
         "roofline": {"kernel": "beam_search_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},
         "cpu_baseline": cpu,
+        "bq_scan": scan,
     }
     print(json.dumps(line), flush=True)
     return 0

@@ -39,6 +39,7 @@ extern "C" {
 #define QV_MAX_DIM 65536
 #define QV_MAX_EF 1024
 #define QV_MAX_DEGREE 4096
+#define QV_MAX_SCAN_K 64
 
 /* bits of the per-vector / per-query status words */
 #define QV_STATUS_NONFINITE 1u      /* encode: the vector holds Inf/NaN, its code is unspecified          */
@@ -135,6 +136,23 @@ void qv_timer_free(qv_timer* t);
 void qv_index_set_timer(qv_index* index, qv_timer* t /* NULL detaches */);
 /* ms: host float [max_calls][3]; returns the number of recorded calls (>= 0) or an error; resets the timer */
 int qv_timer_read(qv_timer* t, float* ms, int max_calls);
+
+/*
+ * Brute-force scan in code space and overlap probe (paper Sec. 6, "Practical compatibility test": compare
+ * the code-ranked top K with the float32-ranked top K on a sample before building an index; Sec. 5.4,
+ * Table 10 reports the same "Top-10 overlap").
+ *    qv_bq_scan: for every query code the K base codes with the smallest (distance, id).
+ *       codes   device, [n][qv_code_words(d)];  qcodes device, [nq][qv_code_words(d)] (qv_encode's layout)
+ *       ids, dist device uint32 [nq][K], sorted by (distance, id), QV_EMPTY padded when n < K
+ *       workspace device, 256-byte aligned, >= qv_bq_scan_workspace_bytes(n, nq, K)
+ *       1 <= K <= QV_MAX_SCAN_K.
+ *    qv_topk_overlap: hits[q] = number of entries of a[q][0..K) that occur in b[q][0..K) (device uint32
+ *       arrays [nq][K]; QV_EMPTY never matches); the probe's figure is sum(hits) / (nq * K).
+ */
+size_t qv_bq_scan_workspace_bytes(int64_t n, int64_t nq, int K);
+int qv_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K, uint32_t* ids,
+               uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream);
+int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* hits, void* stream);
 
 /* Tunables of the search kernel (defaults picked from the shape when 0).  Host only.
  *    visited_slots   slots of the per-query visited table, 1024..28672 (rounded up to a multiple of 1024; to a

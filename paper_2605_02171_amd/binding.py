@@ -48,6 +48,13 @@ _lib.qv_bq_distance.restype = ctypes.c_int
 _lib.qv_bq_distance.argtypes = [_P, _P, _P, _P, ctypes.c_int64, ctypes.c_int, _P, _P]
 _lib.qv_gather_probe.restype = ctypes.c_int
 _lib.qv_gather_probe.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, ctypes.c_int64, _P, _P]
+_lib.qv_bq_scan_workspace_bytes.restype = ctypes.c_size_t
+_lib.qv_bq_scan_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+_lib.qv_bq_scan.restype = ctypes.c_int
+_lib.qv_bq_scan.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, ctypes.c_int64, ctypes.c_int, _P, _P, _P,
+                            ctypes.c_size_t, _P]
+_lib.qv_topk_overlap.restype = ctypes.c_int
+_lib.qv_topk_overlap.argtypes = [_P, _P, ctypes.c_int64, ctypes.c_int, _P, _P]
 _lib.qv_index_load.restype = ctypes.c_int
 _lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P,
                                ctypes.c_uint32]
@@ -160,6 +167,35 @@ def gather_probe(codes: torch.Tensor, d: int, ids: torch.Tensor) -> None:
     sink = torch.zeros(1, dtype=torch.int64, device=codes.device)
     _check(_lib.qv_gather_probe(codes.data_ptr(), codes.shape[0], int(d), ids.data_ptr(), ids.numel(),
                                 sink.data_ptr(), _stream()), "qv_gather_probe")
+
+
+def bq_scan(codes: torch.Tensor, qcodes: torch.Tensor, d: int, K: int):
+    """qv_bq_scan: brute force in code space -> (ids, dist) int32 [nq, K] holding uint32 values."""
+    codes = _dev(codes, torch.int64, "codes")
+    qcodes = _dev(qcodes, torch.int64, "qcodes")
+    cw = code_words(d)
+    if codes.shape[1] != cw or qcodes.shape[1] != cw:
+        raise ValueError("code width does not match d")
+    n, nq = codes.shape[0], qcodes.shape[0]
+    ids = torch.empty((nq, K), dtype=torch.int32, device=codes.device)
+    dist = torch.empty((nq, K), dtype=torch.int32, device=codes.device)
+    need = int(_lib.qv_bq_scan_workspace_bytes(n, nq, K))
+    ws = torch.empty((max(need, 256),), dtype=torch.uint8, device=codes.device)
+    _check(_lib.qv_bq_scan(codes.data_ptr(), n, int(d), qcodes.data_ptr(), nq, int(K), ids.data_ptr(),
+                           dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "qv_bq_scan")
+    return ids, dist
+
+
+def topk_overlap(a: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
+    """qv_topk_overlap: per-query count of ids of a[q] that occur in b[q] (int32 [nq])."""
+    a = _dev(a, torch.int32, "a")
+    b = _dev(b, torch.int32, "b")
+    if a.shape != b.shape or a.dim() != 2:
+        raise ValueError("a and b must both be [nq, K]")
+    hits = torch.empty((a.shape[0],), dtype=torch.int32, device=a.device)
+    _check(_lib.qv_topk_overlap(a.data_ptr(), b.data_ptr(), a.shape[0], a.shape[1], hits.data_ptr(), _stream()),
+           "qv_topk_overlap")
+    return hits
 
 
 class Timer:

@@ -93,6 +93,35 @@ int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids
     return e == hipSuccess ? QV_OK : hip_fail(e, "gather probe launch");
 }
 
+size_t qv_bq_scan_workspace_bytes(int64_t n, int64_t nq, int K) {
+    if (n < 0 || nq < 0 || K < 1 || K > QV_MAX_SCAN_K) return 0;
+    const int64_t chunk = qv::bq_scan_chunk_rows(n);
+    const int64_t nchunks = n > 0 ? (n + chunk - 1) / chunk : 1;
+    return align_up((size_t)nchunks * (size_t)(nq > 0 ? nq : 1) * K * 8, 256);
+}
+
+int qv_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K, uint32_t* ids,
+               uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (n < 0 || n >= 0xFFFFFFFFll || nq < 0 || nq > 64ll * 0x7FFFFFFF || K < 1 || K > QV_MAX_SCAN_K)
+        return QV_ERR_INVALID_ARG;
+    if (nq == 0) return QV_OK;
+    if ((n > 0 && !codes) || !qcodes || !ids || !dist) return QV_ERR_NULL;
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < qv_bq_scan_workspace_bytes(n, nq, K))
+        return QV_ERR_WORKSPACE;
+    hipError_t e = qv::launch_bq_scan(codes, n, d, qcodes, nq, K, static_cast<uint64_t*>(workspace), ids, dist,
+                                      (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "code scan launch");
+}
+
+int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* hits, void* stream) {
+    if (nq < 0 || K < 1) return QV_ERR_INVALID_ARG;
+    if (nq == 0) return QV_OK;
+    if (!a || !b || !hits) return QV_ERR_NULL;
+    hipError_t e = qv::launch_topk_overlap(a, b, nq, K, hits, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "overlap launch");
+}
+
 int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, const uint64_t* codes,
                   const float* vecs, uint32_t entry) {
     if (!out) return QV_ERR_NULL;

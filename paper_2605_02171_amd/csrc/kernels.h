@@ -53,6 +53,11 @@ hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64
                               int64_t npairs, int d, uint32_t* out, hipStream_t stream);
 hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
                                hipStream_t stream);
+int64_t bq_scan_chunk_rows(int64_t n);
+hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K,
+                          uint64_t* partial, uint32_t* ids, uint32_t* dist, hipStream_t stream);
+hipError_t launch_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* out,
+                               hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
 size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef);
