@@ -46,6 +46,9 @@ WORKLOADS = {
     "C3": Workload("C3", 1_000_000, 384, 10_000, "powerlaw", 512, 64, 128, 1.2, 10, (64,), "cosine", 1003, 2003),
     # 3072-d: long codes (768 B)
     "C4": Workload("C4", 1_000_000, 3072, 10_000, "powerlaw", 2048, 64, 128, 1.2, 10, (64,), "cosine", 1004, 2004),
+    # not one of the five contract workloads: low-rank data whose neighbours differ in direction (the regime
+    # the paper calls compatible), used to show the path end to end at a recall that means something
+    "H2": Workload("H2", 1_000_000, 768, 10_000, "lowrank", 32, 64, 128, 1.2, 10, (64,), "cosine", 1012, 2012),
     # structureless boundary case
     "C5": Workload("C5", 1_000_000, 512, 10_000, "gaussian", 0, 64, 128, 1.2, 10, (64,), "l2", 1005, 2005),
 }
@@ -87,6 +90,10 @@ class _Model:
         rng = np.random.Generator(np.random.PCG64(w.seed_base))
         if w.kind == "gaussian":
             return
+        if w.kind == "lowrank":
+            # x = normalise(z A + small noise): z standard normal in `clusters` latent dimensions
+            self.basis = rng.standard_normal((w.clusters, w.d), dtype=np.float32) / np.float32(np.sqrt(w.clusters))
+            return
         c = rng.standard_normal((w.clusters, w.d), dtype=np.float32)
         _normalise_rows(c)
         self.centres = c
@@ -102,6 +109,18 @@ class _Model:
     def draw(self, labels: np.ndarray, seed: list) -> np.ndarray:
         w = self.w
         out = np.empty((labels.shape[0], w.d), dtype=np.float32)
+
+        def fill_lowrank(c, s, e):
+            rng = _chunk_rng(seed, c)
+            z = rng.standard_normal((e - s, w.clusters), dtype=np.float32)
+            g = z @ self.basis
+            g += np.float32(0.05) * rng.standard_normal((e - s, w.d), dtype=np.float32)
+            _normalise_rows(g)
+            out[s:e] = g
+
+        if w.kind == "lowrank":
+            _for_chunks(labels.shape[0], fill_lowrank)
+            return out
 
         def fill(c, s, e):
             g = _chunk_rng(seed, c).standard_normal((e - s, w.d), dtype=np.float32)
@@ -145,6 +164,8 @@ def make_base(w: Workload) -> np.ndarray:
 
         _for_chunks(w.n, fill)
         return out
+    if w.kind == "lowrank":
+        return m.draw(np.zeros(w.n, dtype=np.int64), [w.seed_base, 3])
     if w.kind == "tiny":
         labels = rng.integers(0, w.clusters, size=w.n)
     else:
@@ -160,6 +181,8 @@ def make_queries(w: Workload) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64([w.seed_query, 2]))
     if w.kind == "gaussian":
         return _chunk_rng([w.seed_query, 4], 0).standard_normal((w.nq, w.d), dtype=np.float32)
+    if w.kind == "lowrank":
+        return m.draw(np.zeros(w.nq, dtype=np.int64), [w.seed_query, 4])
     labels = rng.choice(w.clusters, size=w.nq, p=m.prob)
     return m.draw(labels, [w.seed_query, 4])
 
