@@ -224,18 +224,22 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
 
     constexpr int RPP = 64 / G;  // neighbour rows per pass
     constexpr int KW = NW_T > 0 ? (NW_T + G - 1) / G : 1;
-    // passes whose loads are in flight together: all G of them unless that needs > 32 x 64-bit registers
-    constexpr int BATCH = (2 * KW * G <= 32) ? G : (32 / (2 * KW) > 0 ? 32 / (2 * KW) : 1);
+    // passes whose loads are in flight together: all G of them unless that needs > 48 x 64-bit registers
+    constexpr int BATCH = (2 * KW * G <= 48) ? G : (48 / (2 * KW) > 0 ? 48 / (2 * KW) : 1);
     // with all passes in one batch and groups inside a quad, the lane sums are combined by a
     // reduce-scatter over data-parallel primitives and never go through LDS
-    constexpr bool QUAD_REDUCE = NW_T > 0 && BATCH == G && (G == 2 || G == 4);
+    constexpr bool QUAD_REDUCE = NW_T > 0 && BATCH == G && (G == 1 || G == 2 || G == 4);
+    // word assignment inside a group: interleaved (lane s takes words s, s+G, ...) or, when every lane gets
+    // an even number of words, blocked (lane s takes words s*KW .. s*KW+KW-1) so that two words travel
+    // in one 16-byte load
+    constexpr bool BLOCKED = QUAD_REDUCE && NW_T % (2 * G) == 0;
     const int sub = lane % G, grp = lane / G;
     const uint64_t* qsrc = p.qcodes + q * (int64_t)(2 * NW);
     uint64_t qp[KW], qs[KW];
     if constexpr (NW_T > 0) {
 #pragma unroll
         for (int i = 0; i < KW; ++i) {
-            int w = sub + i * G;
+            int w = BLOCKED ? sub * KW + i : sub + i * G;
             qp[i] = w < NW_T ? qsrc[w] : 0ull;
             qs[i] = w < NW_T ? qsrc[NW_T + w] : 0ull;
         }
@@ -267,11 +271,24 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                 const int ri = b * RPP + grp;
                 if (ri < m) {
                     const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW_T);
+                    if constexpr (BLOCKED) {
+                        const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
+                        const uint4* m4 = reinterpret_cast<const uint4*>(row + NW_T + sub * KW);
 #pragma unroll
-                    for (int i = 0; i < KW; ++i) {
-                        int w = sub + i * G;
-                        pv[b][i] = w < NW_T ? row[w] : 0ull;
-                        sv[b][i] = w < NW_T ? row[NW_T + w] : 0ull;
+                        for (int i = 0; i < KW / 2; ++i) {
+                            const uint4 a = r4[i], c = m4[i];
+                            pv[b][2 * i] = ((uint64_t)a.y << 32) | a.x;
+                            pv[b][2 * i + 1] = ((uint64_t)a.w << 32) | a.z;
+                            sv[b][2 * i] = ((uint64_t)c.y << 32) | c.x;
+                            sv[b][2 * i + 1] = ((uint64_t)c.w << 32) | c.z;
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < KW; ++i) {
+                            int w = sub + i * G;
+                            pv[b][i] = w < NW_T ? row[w] : 0ull;
+                            sv[b][i] = w < NW_T ? row[NW_T + w] : 0ull;
+                        }
                     }
                 } else {
 #pragma unroll
@@ -293,7 +310,10 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             // reduce-scatter: afterwards lane `sub` holds the full sum of pass my_b
             uint32_t dist;
             int my_b;
-            if constexpr (G == 2) {
+            if constexpr (G == 1) {
+                dist = part[0];
+                my_b = 0;
+            } else if constexpr (G == 2) {
                 const bool hi = sub & 1;
                 dist = (hi ? part[1] : part[0]) + quad_xor1(hi ? part[0] : part[1]);
                 my_b = hi ? 1 : 0;
@@ -517,9 +537,8 @@ static hipError_t launch_g(const SearchParams& p, int g, hipStream_t stream) {
 }
 
 static int default_lanes_per_row(int nw) {
-    if (nw <= 8) return 2;
-    if (nw <= 16) return 4;
-    if (nw <= 24) return 8;
+    if (nw <= 16) return 2;
+    if (nw <= 24) return 4;
     return 16;
 }
 
@@ -554,6 +573,8 @@ hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStrea
         case 6: return launch_g<6>(p, g, stream);
         case 8: return launch_g<8>(p, g, stream);
         case 12: return launch_g<12>(p, g, stream);
+        case 16: return launch_g<16>(p, g, stream);
+        case 24: return launch_g<24>(p, g, stream);
         case 48: return launch_g<48>(p, g, stream);
         default: return launch_g<0>(p, g, stream);
     }
