@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--visited-slots", type=int, default=0)
     ap.add_argument("--lanes-per-row", type=int, default=0)
     ap.add_argument("--table-format", type=int, default=0)
+    ap.add_argument("--cold-host", action="store_true",
+                    help="keep the float32 vectors in pinned host memory (rerank reads them over PCIe)")
     ap.add_argument("--no-scan", action="store_true", help="skip the brute-force code scan / overlap probe")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one elementwise copy kernel (1 GiB read + 1 GiB write) to calibrate byte counters")
@@ -105,7 +107,11 @@ def main() -> int:
     enc_bytes = w.n * (4 * w.d + w.d // 4)
     log(f"encode base: {enc_ms:.3f} ms, {enc_bytes / enc_ms / 1e6:.0f} GB/s")
 
-    index = qv.Index(adjd, codes, xd, entry)
+    x_cold = None
+    if args.cold_host:
+        x_cold = torch.empty(x.shape, dtype=torch.float32, pin_memory=True)
+        x_cold.copy_(torch.from_numpy(x))
+    index = qv.Index(adjd, codes, x_cold if args.cold_host else xd, entry)
     if args.visited_slots or args.lanes_per_row or args.table_format:
         index.set_tuning(args.visited_slots, args.lanes_per_row, args.table_format)
     ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
@@ -249,6 +255,7 @@ def main() -> int:
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64 popcount (search), f64-accumulated f32 (rerank)", "data": "synthetic",
+        "cold_store": "pinned host memory" if args.cold_host else "HBM",
         "config": {"workload": f"{w.name}: {w.n} x {w.d} {w.kind} unit-norm vectors, {w.nq} queries, "
                                f"graph R={w.R} L={w.L} alpha={w.alpha}, k={k}, ef={ef}"},
         "recall_at_10": recall,

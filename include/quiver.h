@@ -84,7 +84,9 @@ int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids
  *    Creates a host-side handle that remembers the borrowed device buffers; copies nothing.
  *    adj    device, [n][R] uint32, QV_EMPTY = empty slot (rows need not be packed to the left)
  *    codes  device, [n][qv_code_words(d)] uint64 in qv_encode's layout
- *    vecs   device, [n][d] float32 (only read by the rerank)
+ *    vecs   [n][d] float32, only read by the rerank: device memory, or host memory the device can address
+ *           (hipHostMalloc / pinned): the paper's cold store then stays in host RAM and the rerank's ef rows per
+ *           query travel over PCIe
  *    entry  node every search starts from, < n
  *    1 <= R <= QV_MAX_DEGREE, 1 <= n < 2^32 - 1.
  */

@@ -222,12 +222,21 @@ class Timer:
 
 
 class Index:
-    """qv_index_load: borrows adj [n, R] (int32/uint32 bits), codes [n, cw] int64, vecs [n, d] float32."""
+    """qv_index_load: borrows adj [n, R] (int32/uint32 bits), codes [n, cw] int64, vecs [n, d] float32.
+
+    vecs may be a device tensor or a pinned host tensor (``pin_memory=True``): the float32 vectors are the
+    cold data of the method and are only touched by the rerank.
+    """
 
     def __init__(self, adj: torch.Tensor, codes: torch.Tensor, vecs: torch.Tensor, entry: int):
         adj = _dev(adj, torch.int32, "adj")
         codes = _dev(codes, torch.int64, "codes")
-        vecs = _dev(vecs, torch.float32, "vecs")
+        if isinstance(vecs, torch.Tensor) and not vecs.is_cuda and vecs.is_pinned():
+            # cold store kept in pinned host memory: the device addresses it directly, only the rerank reads it
+            if vecs.dtype != torch.float32 or not vecs.is_contiguous():
+                raise TypeError("vecs must be contiguous float32")
+        else:
+            vecs = _dev(vecs, torch.float32, "vecs")
         n, d = vecs.shape
         if adj.shape[0] != n or codes.shape != (n, code_words(d)):
             raise ValueError("adj/codes/vecs shapes do not agree")

@@ -275,3 +275,18 @@ def test_search_workload_shapes_reduced_n(qv, name, n, ef):
     adj, entry = graph.build_graph(x, w.R, 64, w.alpha)
     ref, out = _run_both(qv, x, q, adj, entry, w.k, ef, visit_cap=400)
     _assert_search_equal(qv, ref, out)
+
+
+def test_search_with_cold_vectors_in_pinned_host_memory(qv):
+    # the float32 vectors are only read by the rerank; they may stay in host memory the device can address
+    w = datagen.scaled("C2", n=30_000, nq=64)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 48, 1.2)
+    codes = oracle.encode(x, threads=8)
+    ref = oracle.search(q, adj, codes, x, entry, 10, 64, visit_cap=256, threads=8)
+    cold = torch.empty(x.shape, dtype=torch.float32, pin_memory=True)
+    cold.copy_(torch.from_numpy(x))
+    index = qv.Index(qv.from_numpy_u32(adj), qv.from_numpy_u64(codes), cold, entry)
+    out = qv.search(index, torch.from_numpy(q).cuda(), 10, 64, trace=True, visit_cap=256)
+    torch.cuda.synchronize()
+    _assert_search_equal(qv, ref, out)
