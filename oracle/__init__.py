@@ -61,6 +61,9 @@ def _load():
         lib.orc_cosine_topk.argtypes = [P, ctypes.c_int64, ctypes.c_int, P, ctypes.c_int64, ctypes.c_int, P, ctypes.c_int]
         lib.orc_topk_overlap.restype = ctypes.c_double
         lib.orc_topk_overlap.argtypes = [P, P, ctypes.c_int64, ctypes.c_int]
+        lib.orc_build_graph.restype = ctypes.c_int
+        lib.orc_build_graph.argtypes = [P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                        ctypes.c_uint32, ctypes.c_int64, P]
         _lib = lib
     return _lib
 
@@ -207,3 +210,14 @@ def topk_overlap(a, b) -> float:
     b = _c(b, np.uint32)
     assert a.shape == b.shape
     return float(_load().orc_topk_overlap(_ptr(a), _ptr(b), a.shape[0], a.shape[1]))
+
+
+def build_graph(codes, d: int, R: int, L: int, alpha: float, entry: int, max_batch: int = 1 << 20) -> np.ndarray:
+    """Batch-synchronous construction in code space (Algorithm 1 + bidirectional re-selection) -> adj [n, R]."""
+    codes = _c(codes, np.uint64)
+    n = codes.shape[0]
+    assert codes.shape[1] == code_words(d)
+    adj = np.zeros((n, R), dtype=np.uint32)
+    _check(_load().orc_build_graph(_ptr(codes), n, int(d), int(R), int(L), float(alpha), int(entry), int(max_batch),
+                                   _ptr(adj)), "orc_build_graph")
+    return adj

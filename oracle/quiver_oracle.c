@@ -472,3 +472,165 @@ double orc_topk_overlap(const uint32_t *a, const uint32_t *b, int64_t nq, int K)
         }
     return (double)hits / (double)(nq * K);
 }
+
+/* ------------------------------------------------------------------ */
+/* Graph construction in code space (Sec. 3.2, Algorithm 1 "BQ-Vamana  */
+/* Edge Selection" with the bidirectional re-selection of Sec. 2.2).   */
+/*                                                                     */
+/* The paper inserts nodes concurrently under per-node locks (Sec. 4.1)*/
+/* which has no single defined result.  The reading taken here is the  */
+/* batch-synchronous one, whose result is a function of the inputs:    */
+/*   nodes are inserted in id order, in batches of max(1, done/50)     */
+/*   (at most max_batch); every node of a batch searches the graph as  */
+/*   it stood before the batch (beam width L, from `entry`), takes as  */
+/*   candidates the final list plus its current out-neighbours, and    */
+/*   selects its out-edges by Algorithm 1; then every node b that was  */
+/*   selected receives the selecting nodes as in-edge candidates: if   */
+/*   they fit in the row they are added, otherwise the row is          */
+/*   re-selected by Algorithm 1 from (old row U new candidates).       */
+/*   A node considers at most ORC_MAX_NEW_IN_EDGES new candidates per  */
+/*   batch: the nearest ones by (distance, id).  Only hub nodes that   */
+/*   hundreds of batch members select at once ever reach that cap.     */
+/* The order of ids inside a row carries no meaning (the search does   */
+/* not depend on it); rows are compared as sets.                       */
+/* ------------------------------------------------------------------ */
+#define ORC_MAX_NEW_IN_EDGES 192
+
+typedef struct {
+    uint32_t dist;
+    uint32_t id;
+} cand_t;
+
+static int cand_cmp(const void *a, const void *b) {
+    const cand_t *x = (const cand_t *)a, *y = (const cand_t *)b;
+    if (x->dist != y->dist) return x->dist < y->dist ? -1 : 1;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return 0;
+}
+
+/* Algorithm 1: cand sorted by (dist to t, id), without t and without repeats; returns |selected| */
+static int select_edges(const uint64_t *codes, int cw, int d, const cand_t *cand, int n_cand, int R, double alpha,
+                        uint32_t *selected) {
+    int ns = 0;
+    for (int i = 0; i < n_cand && ns < R; ++i) {
+        int keep = 1;
+        for (int j = 0; j < ns && keep; ++j) {
+            uint32_t dcs = orc_sm_distance(codes + (int64_t)cand[i].id * cw, codes + (int64_t)selected[j] * cw, d);
+            if (!((double)cand[i].dist <= alpha * (double)dcs)) keep = 0;
+        }
+        if (keep) selected[ns++] = cand[i].id;
+    }
+    return ns;
+}
+
+int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                    int64_t max_batch, uint32_t *adj) {
+    if (!codes || !adj || n < 1 || d < 1 || R < 1 || L < 1 || alpha < 1.0 || (int64_t)entry >= n || max_batch < 1)
+        return ORC_ERR_ARG;
+    int cw = orc_code_words(d);
+    for (int64_t i = 0; i < n * R; ++i) adj[i] = ORC_EMPTY;
+    uint8_t *visited = (uint8_t *)calloc((size_t)n, 1);
+    uint32_t *touched = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n);
+    entry_t *pool = (entry_t *)malloc(sizeof(entry_t) * (size_t)(L + 1));
+    uint32_t *cid = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)L);
+    uint32_t *cds = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)L);
+    uint32_t counters[3];
+    int64_t done = 0;
+    int rc = ORC_OK;
+    while (done < n && rc == ORC_OK) {
+        int64_t bs = done / 50;
+        if (bs < 1) bs = 1;
+        if (bs > max_batch) bs = max_batch;
+        if (done + bs > n) bs = n - done;
+        uint32_t *fwd = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(bs * R));
+        int *nfwd = (int *)malloc(sizeof(int) * (size_t)bs);
+        /* 1. searches and selections against the graph as it stands */
+        for (int64_t i = 0; i < bs && rc == ORC_OK; ++i) {
+            uint32_t t = (uint32_t)(done + i);
+            rc = beam_search_one(codes + (int64_t)t * cw, n, d, R, adj, codes, entry, L, visited, pool, touched, cid,
+                                 cds, NULL, 0, counters);
+            if (rc != ORC_OK) break;
+            cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(L + R));
+            int nc = 0;
+            for (int j = 0; j < (int)counters[0]; ++j)
+                if (cid[j] != t) {
+                    cand[nc].dist = cds[j];
+                    cand[nc++].id = cid[j];
+                }
+            for (int j = 0; j < R; ++j) {
+                uint32_t v = adj[(int64_t)t * R + j];
+                if (v == ORC_EMPTY || v == t) continue;
+                int have = 0;
+                for (int k = 0; k < nc; ++k) have |= cand[k].id == v;
+                if (!have) {
+                    cand[nc].dist = orc_sm_distance(codes + (int64_t)t * cw, codes + (int64_t)v * cw, d);
+                    cand[nc++].id = v;
+                }
+            }
+            qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
+            nfwd[i] = select_edges(codes, cw, d, cand, nc, R, alpha, fwd + i * R);
+            free(cand);
+        }
+        /* 2. publish the rows of the batch */
+        for (int64_t i = 0; i < bs && rc == ORC_OK; ++i)
+            for (int j = 0; j < R; ++j) adj[(done + i) * R + j] = j < nfwd[i] ? fwd[i * R + j] : ORC_EMPTY;
+        /* 3. in-edges: for every target, all nodes of the batch that selected it */
+        for (int64_t b = 0; b < n && rc == ORC_OK; ++b) {
+            cand_t *cand = NULL;
+            int nc = 0, deg = 0, n_new = 0;
+            for (int64_t i = 0; i < bs; ++i) {
+                int chose = 0;
+                for (int j = 0; j < nfwd[i]; ++j) chose |= fwd[i * R + j] == (uint32_t)b;
+                if (!chose || done + i == b) continue;
+                if (!cand) {
+                    cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(R + bs));
+                    for (int j = 0; j < R; ++j) {
+                        uint32_t v = adj[b * R + j];
+                        if (v == ORC_EMPTY) continue;
+                        cand[nc].id = v;
+                        cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)v * cw, d);
+                    }
+                    deg = nc;
+                }
+                uint32_t t = (uint32_t)(done + i);
+                int have = 0;
+                for (int k = 0; k < nc; ++k) have |= cand[k].id == t;
+                if (have) continue;
+                cand[nc].id = t;
+                cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)t * cw, d);
+                n_new++;
+            }
+            if (!cand) continue;
+            if (n_new > ORC_MAX_NEW_IN_EDGES) { /* keep the nearest new candidates only */
+                qsort(cand + deg, (size_t)n_new, sizeof(cand_t), cand_cmp);
+                n_new = ORC_MAX_NEW_IN_EDGES;
+                nc = deg + n_new;
+            }
+            if (n_new > 0) {
+                if (deg + n_new <= R) {
+                    int slot = 0;
+                    for (int k = deg; k < nc; ++k) {
+                        while (adj[b * R + slot] != ORC_EMPTY) slot++;
+                        adj[b * R + slot] = cand[k].id;
+                    }
+                } else {
+                    uint32_t *sel = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)R);
+                    qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
+                    int ns = select_edges(codes, cw, d, cand, nc, R, alpha, sel);
+                    for (int j = 0; j < R; ++j) adj[b * R + j] = j < ns ? sel[j] : ORC_EMPTY;
+                    free(sel);
+                }
+            }
+            free(cand);
+        }
+        free(fwd);
+        free(nfwd);
+        done += bs;
+    }
+    free(visited);
+    free(touched);
+    free(pool);
+    free(cid);
+    free(cds);
+    return rc;
+}

@@ -65,6 +65,19 @@ def _p(a):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def build_graph_from_codes(codes: np.ndarray, d: int, R: int, L: int, alpha: float, entry: int,
+                           threads: int | None = None, max_batch: int = 1 << 20) -> np.ndarray:
+    """The generator's construction on given codes (uint64 [n, 2*ceil(d/64)]) and entry -> adj [n, R]."""
+    lib = _load()
+    codes = np.ascontiguousarray(codes, dtype=np.uint64)
+    n = codes.shape[0]
+    adj = np.empty((n, R), dtype=np.uint32)
+    rc = lib.vh_build(_p(codes), n, d, R, L, float(alpha), int(entry), _p(adj), threads or host_threads(), None,
+                      0.02, max_batch)
+    assert rc == 0, rc
+    return adj
+
+
 def build_graph(x: np.ndarray, R: int, L: int, alpha: float, threads: int | None = None,
                 progress_path: str | None = None, max_batch: int = 1 << 20):
     """float32 [n, d] -> (adj uint32 [n, R], entry).  Deterministic for given inputs and parameters."""
@@ -92,7 +105,7 @@ def cache_dir() -> str:
 def cached_graph(tag: str, x: np.ndarray, R: int, L: int, alpha: float, progress_path: str | None = None):
     """build_graph with a file cache keyed by the parameters and a digest of a sample of the data."""
     h = hashlib.sha256()
-    h.update(repr((tag, x.shape, R, L, alpha)).encode())
+    h.update(repr(("v2", tag, x.shape, R, L, alpha)).encode())
     step = max(1, x.shape[0] // 64)
     h.update(np.ascontiguousarray(x[::step]).tobytes())
     path = os.path.join(cache_dir(), f"graph_{tag}_{h.hexdigest()[:16]}.npz")
