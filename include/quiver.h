@@ -35,6 +35,7 @@ extern "C" {
 #define QV_ERR_WORKSPACE (-6)   /* workspace NULL, misaligned or too small             */
 #define QV_ERR_HIP (-7)         /* a HIP runtime call failed (see qv_last_hip_error)   */
 #define QV_ERR_NOMEM (-8)       /* host allocation failed                              */
+#define QV_ERR_UNSUPPORTED (-9) /* the shape is outside what this entry point handles */
 
 #define QV_MAX_DIM 65536
 #define QV_MAX_EF 1024
@@ -155,6 +156,26 @@ size_t qv_bq_scan_workspace_bytes(int64_t n, int64_t nq, int K);
 int qv_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K, uint32_t* ids,
                uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream);
 int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* hits, void* stream);
+
+/*
+ * Graph construction in code space (paper Sec. 3.2, Algorithm 1 "BQ-Vamana Edge Selection": candidates
+ * sorted by distance to the target t, c is kept iff dist(c,t) <= alpha * dist(c,s) for every s kept before
+ * it, at most R kept; Sec. 2.2: when t selects b, t becomes a candidate of b and b's row is re-selected).
+ * Batch-synchronous reading (the paper's lock-based concurrent insertion, Sec. 4.1, has no single defined
+ * result): nodes enter in id order in batches of max(1, done/50) (at most max_batch); every node of a
+ * batch searches the graph as it stood before the batch (beam width L from `entry`) and selects its
+ * out-edges from its final list plus its current out-neighbours; then every selected node takes the
+ * selecting nodes (at most the 192 nearest per batch) into its row if they fit and re-selects the row
+ * from (old row U new candidates) otherwise.  The order of ids inside a row carries no meaning.
+ *    codes   device, [n][qv_code_words(d)]         adj  device, [n][R] uint32, written in full
+ *    1 <= R <= 64, 1 <= L <= 192, alpha >= 1, entry < n; ceil(d/64) must be one of 2, 6, 8, 12, 16
+ *    (d = 65..128, 321..384, 449..512, 705..768, 961..1024); other widths: QV_ERR_UNSUPPORTED
+ *    workspace device, 256-byte aligned, >= qv_build_workspace_bytes(n, d, R, L, max_batch)
+ * All work is queued on `stream`; the call returns when everything is queued.
+ */
+size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch);
+int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                   int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Tunables of the search kernel (defaults picked from the shape when 0).  Host only.
  *    visited_slots   slots of the per-query visited table, 1024..28672 (rounded up to a multiple of 1024; to a

@@ -574,33 +574,39 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
         /* 2. publish the rows of the batch */
         for (int64_t i = 0; i < bs && rc == ORC_OK; ++i)
             for (int j = 0; j < R; ++j) adj[(done + i) * R + j] = j < nfwd[i] ? fwd[i * R + j] : ORC_EMPTY;
-        /* 3. in-edges: for every target, all nodes of the batch that selected it */
-        for (int64_t b = 0; b < n && rc == ORC_OK; ++b) {
-            cand_t *cand = NULL;
-            int nc = 0, deg = 0, n_new = 0;
-            for (int64_t i = 0; i < bs; ++i) {
-                int chose = 0;
-                for (int j = 0; j < nfwd[i]; ++j) chose |= fwd[i * R + j] == (uint32_t)b;
-                if (!chose || done + i == b) continue;
-                if (!cand) {
-                    cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(R + bs));
-                    for (int j = 0; j < R; ++j) {
-                        uint32_t v = adj[b * R + j];
-                        if (v == ORC_EMPTY) continue;
-                        cand[nc].id = v;
-                        cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)v * cw, d);
-                    }
-                    deg = nc;
-                }
-                uint32_t t = (uint32_t)(done + i);
-                int have = 0;
-                for (int k = 0; k < nc; ++k) have |= cand[k].id == t;
+        /* 3. in-edges: for every target, all nodes of the batch that selected it.
+         *    The (target, source) pairs are sorted so that each target's sources sit together. */
+        int64_t n_pairs = 0;
+        for (int64_t i = 0; i < bs; ++i) n_pairs += nfwd[i];
+        cand_t *pairs = (cand_t *)malloc(sizeof(cand_t) * (size_t)(n_pairs > 0 ? n_pairs : 1));
+        n_pairs = 0;
+        for (int64_t i = 0; i < bs; ++i)
+            for (int j = 0; j < nfwd[i]; ++j) {
+                pairs[n_pairs].dist = fwd[i * R + j];          /* target (sort key) */
+                pairs[n_pairs++].id = (uint32_t)(done + i);    /* source */
+            }
+        qsort(pairs, (size_t)n_pairs, sizeof(cand_t), cand_cmp);
+        for (int64_t p0 = 0; p0 < n_pairs && rc == ORC_OK;) {
+            int64_t b = pairs[p0].dist, p1 = p0;
+            while (p1 < n_pairs && pairs[p1].dist == (uint32_t)b) p1++;
+            cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(R + (p1 - p0)));
+            int nc = 0, deg, n_new = 0;
+            for (int j = 0; j < R; ++j) {
+                uint32_t v = adj[b * R + j];
+                if (v == ORC_EMPTY) continue;
+                cand[nc].id = v;
+                cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)v * cw, d);
+            }
+            deg = nc;
+            for (int64_t p = p0; p < p1; ++p) {
+                uint32_t t = pairs[p].id;
+                int have = t == (uint32_t)b;
+                for (int k = 0; k < deg; ++k) have |= cand[k].id == t;
                 if (have) continue;
                 cand[nc].id = t;
                 cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)t * cw, d);
                 n_new++;
             }
-            if (!cand) continue;
             if (n_new > ORC_MAX_NEW_IN_EDGES) { /* keep the nearest new candidates only */
                 qsort(cand + deg, (size_t)n_new, sizeof(cand_t), cand_cmp);
                 n_new = ORC_MAX_NEW_IN_EDGES;
@@ -622,7 +628,9 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
                 }
             }
             free(cand);
+            p0 = p1;
         }
+        free(pairs);
         free(fwd);
         free(nfwd);
         done += bs;

@@ -55,6 +55,11 @@ _lib.qv_bq_scan.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, ctypes.c_int64
                             ctypes.c_size_t, _P]
 _lib.qv_topk_overlap.restype = ctypes.c_int
 _lib.qv_topk_overlap.argtypes = [_P, _P, ctypes.c_int64, ctypes.c_int, _P, _P]
+_lib.qv_build_workspace_bytes.restype = ctypes.c_size_t
+_lib.qv_build_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64]
+_lib.qv_build_graph.restype = ctypes.c_int
+_lib.qv_build_graph.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                ctypes.c_uint32, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]
 _lib.qv_index_load.restype = ctypes.c_int
 _lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P,
                                ctypes.c_uint32]
@@ -196,6 +201,21 @@ def topk_overlap(a: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
     _check(_lib.qv_topk_overlap(a.data_ptr(), b.data_ptr(), a.shape[0], a.shape[1], hits.data_ptr(), _stream()),
            "qv_topk_overlap")
     return hits
+
+
+def build_graph(codes: torch.Tensor, d: int, R: int, L: int, alpha: float, entry: int,
+                max_batch: int = 1 << 20) -> torch.Tensor:
+    """qv_build_graph: batch-synchronous construction in code space -> adj int32 [n, R] (uint32 bits)."""
+    codes = _dev(codes, torch.int64, "codes")
+    n = codes.shape[0]
+    if codes.shape[1] != code_words(d):
+        raise ValueError("code width does not match d")
+    need = int(_lib.qv_build_workspace_bytes(n, int(d), int(R), int(L), int(max_batch)))
+    ws = torch.empty((max(need, 256),), dtype=torch.uint8, device=codes.device)
+    adj = torch.empty((n, R), dtype=torch.int32, device=codes.device)
+    _check(_lib.qv_build_graph(codes.data_ptr(), n, int(d), int(R), int(L), float(alpha), int(entry), int(max_batch),
+                               adj.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "qv_build_graph")
+    return adj
 
 
 class Timer:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquiver_hip.so")
-SOURCES = ["api.hip", "encode.hip", "search.hip", "rerank.hip", "scan.hip"]
+SOURCES = ["api.hip", "encode.hip", "search.hip", "rerank.hip", "scan.hip", "build.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -44,7 +44,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose and rest:
             print("\n".join(rest), file=sys.stderr)
 
-    with ThreadPoolExecutor(5) as ex:
+    with ThreadPoolExecutor(6) as ex:
         list(ex.map(compile_one, zip(SOURCES, objs)))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)
     for o in objs:

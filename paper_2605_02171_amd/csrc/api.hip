@@ -122,6 +122,27 @@ int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uin
     return e == hipSuccess ? QV_OK : hip_fail(e, "overlap launch");
 }
 
+static bool build_args_ok(int64_t n, int d, int R, int L) {
+    return n >= 1 && n < 0xFFFFFFFFll && R >= 1 && R <= 64 && L >= 1 && L <= 192 && d >= 1 && d <= QV_MAX_DIM;
+}
+
+size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch) {
+    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !qv::build_supports_width((d + 63) / 64)) return 0;
+    return qv::build_workspace_bytes(n, R, L, max_batch);
+}
+
+int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                   int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !(alpha >= 1.0) || (int64_t)entry >= n) return QV_ERR_INVALID_ARG;
+    if (!qv::build_supports_width((d + 63) / 64)) return QV_ERR_UNSUPPORTED;
+    if (!codes || !adj) return QV_ERR_NULL;
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < qv::build_workspace_bytes(n, R, L, max_batch))
+        return QV_ERR_WORKSPACE;
+    hipError_t e = qv::build_graph(codes, n, d, R, L, alpha, entry, max_batch, adj, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "graph construction");
+}
+
 int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, const uint64_t* codes,
                   const float* vecs, uint32_t entry) {
     if (!out) return QV_ERR_NULL;
@@ -275,6 +296,7 @@ const char* qv_strerror(int code) {
         case QV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case QV_ERR_HIP: return "HIP runtime error";
         case QV_ERR_NOMEM: return "host allocation failed";
+        case QV_ERR_UNSUPPORTED: return "shape not supported by this entry point";
         default: return "unknown error code";
     }
 }

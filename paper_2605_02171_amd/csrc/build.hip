@@ -1,0 +1,322 @@
+// Graph construction in code space on the GPU (paper Sec. 3.2, Algorithm 1 "BQ-Vamana Edge Selection",
+// with the bidirectional re-selection of Sec. 2.2), batch-synchronous reading:
+//   nodes are inserted in id order in batches of max(1, done/50); every node of a batch searches the
+//   graph as it stood before the batch (beam width L, the library's own beam-search kernel), takes as
+//   candidates its final list plus its current out-neighbours and selects its out-edges by Algorithm 1;
+//   then every selected node b receives the selecting nodes as in-edge candidates (at most the 192
+//   nearest per batch): added if they fit in the row, otherwise the row is re-selected by Algorithm 1
+//   from (old row U new candidates).
+// The paper's own construction is lock-based and concurrent (Sec. 4.1) and has no single defined
+// result; this reading is a function of its inputs, so it can be checked bit for bit.
+//
+// Per batch: beam_search_kernel -> forward_select_kernel (one wave per new node) -> radix sort of the
+// (target, source) pairs (hipCUB) -> reverse_kernel (one wave per target).  Algorithm 1 runs with one
+// lane per already selected neighbour: the candidate's code is wave-uniform (scalar loads), every lane
+// keeps "its" selected code in registers and computes one distance, a ballot decides.
+#include <hip/hip_runtime.h>
+#include <hipcub/hipcub.hpp>
+#include <stdint.h>
+
+#include "kernels.h"
+
+namespace qv {
+
+constexpr uint64_t B_NONE = ~0ull;
+constexpr int BUF = 256;       // candidate keys (dist << 32 | id) a wave can sort
+constexpr int MAX_NEW = 192;   // new in-edge candidates a node considers per batch
+
+__device__ __forceinline__ void bsync() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// ascending bitonic sort of buf[0..m), m in {64, 128, 256}, by one wave
+__device__ void sort_keys(uint64_t* buf, int m, int lane) {
+    for (int k = 2; k <= m; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int pp = lane; pp < (m >> 1); pp += 64) {
+                const int i = ((pp & ~(j - 1)) << 1) | (pp & (j - 1));
+                const int l = i | j;
+                const uint64_t a = buf[i], b = buf[l];
+                const bool up = (i & k) == 0;
+                if ((a > b) == up) { buf[i] = b; buf[l] = a; }
+            }
+            bsync();
+        }
+    }
+}
+
+__device__ __forceinline__ int pow2_at_least(int c) { return c <= 64 ? 64 : (c <= 128 ? 128 : 256); }
+
+// distance between a wave-uniform code (scalar pointer) and a per-lane code in memory
+template <int NW_T>
+__device__ __forceinline__ uint32_t dist_uniform_vs_row(const uint32_t* __restrict__ cu, const uint64_t* __restrict__ codes,
+                                                        uint32_t v) {
+    constexpr int DW = 2 * NW_T;
+    const uint32_t* r = reinterpret_cast<const uint32_t*>(codes + (int64_t)v * (2 * NW_T));
+    uint32_t c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+    for (int w = 0; w < DW; ++w) {
+        const uint32_t x = cu[w] ^ r[w], sv = r[DW + w], su = cu[DW + w];
+        c1 += __popc(x);
+        c2 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, su, 0xE0));
+        c3 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, su, 0x80));
+    }
+    return c1 + c2 + 2u * c3;
+}
+
+// Algorithm 1 over buf[0..count) (sorted ascending, ids distinct, self excluded).  sel[0..ns) receives the ids.
+template <int NW_T>
+__device__ int select_edges_dev(const uint64_t* __restrict__ codes, const uint64_t* buf, int count, int R, double alpha,
+                                uint32_t* sel, int lane) {
+    constexpr int DW = 2 * NW_T;
+    uint32_t sc[2 * DW];  // the code of the neighbour this lane stands for
+#pragma unroll
+    for (int w = 0; w < 2 * DW; ++w) sc[w] = 0;
+    int ns = 0;
+    for (int i = 0; i < count; ++i) {
+        const uint64_t key = buf[i];
+        const uint32_t c = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)key);
+        const uint32_t dct = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(key >> 32));
+        const uint32_t* crow = reinterpret_cast<const uint32_t*>(codes + (int64_t)c * (2 * NW_T));  // wave-uniform
+        uint32_t c1 = 0, c2 = 0, c3 = 0;
+#pragma unroll
+        for (int w = 0; w < DW; ++w) {
+            const uint32_t x = crow[w] ^ sc[w], sv = crow[DW + w], ss = sc[DW + w];
+            c1 += __popc(x);
+            c2 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, ss, 0xE0));
+            c3 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, ss, 0x80));
+        }
+        const uint32_t dcs = c1 + c2 + 2u * c3;
+        const bool viol = lane < ns && !((double)dct <= alpha * (double)dcs);
+        if (!__any(viol)) {
+            if (lane == ns) {
+#pragma unroll
+                for (int w = 0; w < 2 * DW; ++w) sc[w] = crow[w];
+            }
+            if (lane == 0) sel[ns] = c;
+            ns++;
+            if (ns == R) break;
+        }
+    }
+    bsync();
+    return ns;
+}
+
+struct BuildParams {
+    const uint64_t* codes;
+    uint32_t* adj;
+    int64_t n;
+    int R, L;
+    double alpha;
+    int64_t done, bs;
+    const uint32_t* cand_ids;   // [bs][L]
+    const uint32_t* cand_dist;  // [bs][L]
+    const uint32_t* n_cand;     // [bs]
+    uint64_t* pairs;            // [bs*R] (target << 32 | source), B_NONE where unused
+};
+
+template <int NW_T>
+__global__ __launch_bounds__(64) void forward_select_kernel(BuildParams p) {
+    __shared__ uint64_t buf[BUF];
+    __shared__ uint32_t sel[64];
+    const int lane = threadIdx.x;
+    const int64_t i = blockIdx.x;
+    const uint32_t t = (uint32_t)(p.done + i);
+    const int nc = (int)p.n_cand[i];
+    int removed = 0;
+    for (int e = lane; e < BUF; e += 64) {
+        uint64_t key = B_NONE;
+        if (e < nc) {
+            const uint32_t id = p.cand_ids[i * p.L + e];
+            if (id != t) key = ((uint64_t)p.cand_dist[i * p.L + e] << 32) | id;
+        }
+        buf[e] = key;
+        removed += __popcll(__ballot(e < nc && key == B_NONE));
+    }
+    int total = nc;
+    // current out-neighbours (only a node that was reachable before its own turn has any)
+    const uint32_t v = lane < p.R ? p.adj[(int64_t)t * p.R + lane] : EMPTY_ID;
+    const bool has = v != EMPTY_ID && v != t;
+    bsync();
+    if (__any(has)) {
+        bool dup = false;
+        for (int e = 0; e < nc; ++e) dup |= (uint32_t)buf[e] == v;
+        const bool add = has && !dup;
+        const uint32_t* ct = reinterpret_cast<const uint32_t*>(p.codes + (int64_t)t * (2 * NW_T));
+        const uint32_t dv = add ? dist_uniform_vs_row<NW_T>(ct, p.codes, v) : 0u;
+        const uint64_t am = __ballot(add);
+        const int pos = total + __popcll(am & ((1ull << lane) - 1ull));
+        if (add && pos < BUF) buf[pos] = ((uint64_t)dv << 32) | v;
+        total += __popcll(am);
+        bsync();
+    }
+    sort_keys(buf, pow2_at_least(total), lane);
+    const int ns = select_edges_dev<NW_T>(p.codes, buf, total - removed, p.R, p.alpha, sel, lane);
+    if (lane < p.R) {
+        const uint32_t s = lane < ns ? sel[lane] : EMPTY_ID;
+        p.adj[(int64_t)t * p.R + lane] = s;
+        p.pairs[i * p.R + lane] = lane < ns ? (((uint64_t)s << 32) | t) : B_NONE;
+    }
+}
+
+template <int NW_T>
+__global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64_t* __restrict__ sorted,
+                                                     int64_t n_pairs) {
+    __shared__ uint64_t buf[BUF];
+    __shared__ uint32_t sel[64];
+    __shared__ uint32_t rowcopy[64];
+    const int lane = threadIdx.x;
+    const int64_t p0 = blockIdx.x;
+    const uint64_t first = sorted[p0];
+    if (first == B_NONE) return;
+    const uint32_t b = (uint32_t)(first >> 32);
+    if (p0 > 0 && (uint32_t)(sorted[p0 - 1] >> 32) == b) return;  // not the start of b's run
+
+    const uint32_t v = lane < p.R ? p.adj[(int64_t)b * p.R + lane] : EMPTY_ID;
+    rowcopy[lane] = v;
+    const uint64_t occupied = __ballot(v != EMPTY_ID);
+    const int deg = __popcll(occupied);
+    const uint32_t* cb = reinterpret_cast<const uint32_t*>(p.codes + (int64_t)b * (2 * NW_T));  // wave-uniform
+    bsync();
+
+    int cnt = 0;  // new candidates in buf[0..cnt)
+    for (int64_t q = p0;; q += 64) {
+        const uint64_t k = q + lane < n_pairs ? sorted[q + lane] : B_NONE;
+        const bool in_run = k != B_NONE && (uint32_t)(k >> 32) == b;
+        const uint32_t t = (uint32_t)k;
+        bool ok = in_run && t != b;
+        for (int j = 0; j < p.R; ++j) ok &= rowcopy[j] != t;
+        const uint32_t dt = ok ? dist_uniform_vs_row<NW_T>(cb, p.codes, t) : 0u;
+        const uint64_t om = __ballot(ok);
+        const int m = __popcll(om);
+        if (cnt + m > BUF) {  // make room: keep the nearest MAX_NEW seen so far
+            for (int e = cnt + lane; e < BUF; e += 64) buf[e] = B_NONE;
+            bsync();
+            sort_keys(buf, BUF, lane);
+            cnt = MAX_NEW;
+        }
+        if (ok) buf[cnt + __popcll(om & ((1ull << lane) - 1ull))] = ((uint64_t)dt << 32) | t;
+        cnt += m;
+        bsync();
+        if (__ballot(in_run) != ~0ull) break;  // the run ended inside this chunk
+    }
+    if (cnt > MAX_NEW) {
+        for (int e = cnt + lane; e < BUF; e += 64) buf[e] = B_NONE;
+        bsync();
+        sort_keys(buf, BUF, lane);
+        cnt = MAX_NEW;
+    }
+    if (cnt == 0) return;
+    if (deg + cnt <= p.R) {  // room for all: fill the free slots
+        const bool free_slot = lane < p.R && v == EMPTY_ID;
+        const int r = __popcll(__ballot(free_slot) & ((1ull << lane) - 1ull));
+        if (free_slot && r < cnt) p.adj[(int64_t)b * p.R + lane] = (uint32_t)buf[r];
+        return;
+    }
+    // re-select from (old row U new candidates)
+    const bool old = lane < p.R && v != EMPTY_ID;
+    const uint32_t dv = old ? dist_uniform_vs_row<NW_T>(cb, p.codes, v) : 0u;
+    if (old) buf[cnt + __popcll(occupied & ((1ull << lane) - 1ull))] = ((uint64_t)dv << 32) | v;
+    const int total = cnt + deg;  // <= MAX_NEW + 64 = BUF
+    const int m2 = pow2_at_least(total);
+    for (int e = total + lane; e < m2; e += 64) buf[e] = B_NONE;
+    bsync();
+    sort_keys(buf, m2, lane);
+    const int ns = select_edges_dev<NW_T>(p.codes, buf, total, p.R, p.alpha, sel, lane);
+    if (lane < p.R) p.adj[(int64_t)b * p.R + lane] = lane < ns ? sel[lane] : EMPTY_ID;
+}
+
+size_t build_sort_temp_bytes(int64_t max_pairs) {
+    size_t bytes = 0;
+    uint64_t* none = nullptr;
+    (void)hipcub::DeviceRadixSort::SortKeys(nullptr, bytes, none, none, (int)max_pairs, 0, 64, (hipStream_t)0);
+    return bytes;
+}
+
+bool build_supports_width(int nw) { return nw == 2 || nw == 6 || nw == 8 || nw == 12 || nw == 16; }
+
+template <int NW_T>
+static hipError_t launch_batch(const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
+                               hipStream_t stream) {
+    hipLaunchKernelGGL(forward_select_kernel<NW_T>, dim3((unsigned)bp.bs), dim3(64), 0, stream, bp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t n_pairs = bp.bs * bp.R;
+    e = hipcub::DeviceRadixSort::SortKeys(temp, temp_bytes, bp.pairs, sorted, (int)n_pairs, 0, 64, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(reverse_kernel<NW_T>, dim3((unsigned)n_pairs), dim3(64), 0, stream, bp, sorted, n_pairs);
+    return hipGetLastError();
+}
+
+hipError_t launch_build_batch(int nw, const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
+                              hipStream_t stream) {
+    switch (nw) {
+        case 2: return launch_batch<2>(bp, sorted, temp, temp_bytes, stream);
+        case 6: return launch_batch<6>(bp, sorted, temp, temp_bytes, stream);
+        case 8: return launch_batch<8>(bp, sorted, temp, temp_bytes, stream);
+        case 12: return launch_batch<12>(bp, sorted, temp, temp_bytes, stream);
+        case 16: return launch_batch<16>(bp, sorted, temp, temp_bytes, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// ---- host loop -------------------------------------------------------------------------------
+
+static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
+int64_t build_max_batch(int64_t n, int64_t max_batch) {
+    int64_t b = n / 50;
+    if (b < 1) b = 1;
+    if (b > max_batch) b = max_batch;
+    return b;
+}
+
+size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch) {
+    const int64_t mb = build_max_batch(n, max_batch);
+    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) + up256((size_t)mb * R * 8) * 2 +
+           up256(build_sort_temp_bytes(mb * R)) + 256;
+}
+
+hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                       int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream) {
+    const int nw = (d + 63) / 64;
+    const int64_t mb = build_max_batch(n, max_batch);
+    char* ws = static_cast<char*>(workspace);
+    uint32_t* cand_ids = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * L * 4);
+    uint32_t* cand_dist = reinterpret_cast<uint32_t*>(ws);  ws += up256((size_t)mb * L * 4);
+    uint32_t* n_cand = reinterpret_cast<uint32_t*>(ws);     ws += up256((size_t)mb * 4);
+    uint64_t* pairs = reinterpret_cast<uint64_t*>(ws);      ws += up256((size_t)mb * R * 8);
+    uint64_t* sorted = reinterpret_cast<uint64_t*>(ws);     ws += up256((size_t)mb * R * 8);
+    const size_t temp_bytes = build_sort_temp_bytes(mb * R);
+    void* temp = ws;
+
+    hipError_t e = hipMemsetAsync(adj, 0xFF, (size_t)n * R * 4, stream);
+    if (e != hipSuccess) return e;
+    SearchParams sp{};
+    sp.adj = adj; sp.codes = codes; sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
+    sp.cand_ids = cand_ids; sp.cand_dist = cand_dist; sp.n_cand = n_cand;
+    sp.n_expanded = nullptr; sp.n_evals = nullptr; sp.status = nullptr; sp.visit_order = nullptr; sp.visit_cap = 0;
+    plan_visited_table(sp, (uint32_t)(96 * L + 2048), true);
+    if (sp.vis_regions == 0 && sp.vis_slots > 8192) plan_visited_table(sp, 8192, false);
+    BuildParams bp{};
+    bp.codes = codes; bp.adj = adj; bp.n = n; bp.R = R; bp.L = L; bp.alpha = alpha;
+    bp.cand_ids = cand_ids; bp.cand_dist = cand_dist; bp.n_cand = n_cand; bp.pairs = pairs;
+    for (int64_t done = 0; done < n;) {
+        int64_t bs = done / 50;
+        if (bs < 1) bs = 1;
+        if (bs > mb) bs = mb;
+        if (done + bs > n) bs = n - done;
+        sp.qcodes = codes + done * (int64_t)(2 * nw);
+        sp.nq = bs;
+        e = launch_beam_search(sp, 0, stream);
+        if (e != hipSuccess) return e;
+        bp.done = done; bp.bs = bs;
+        e = launch_build_batch(nw, bp, sorted, temp, temp_bytes, stream);
+        if (e != hipSuccess) return e;
+        done += bs;
+    }
+    return hipSuccess;
+}
+
+}  // namespace qv

@@ -58,6 +58,10 @@ hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_
                           uint64_t* partial, uint32_t* ids, uint32_t* dist, hipStream_t stream);
 hipError_t launch_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* out,
                                hipStream_t stream);
+bool build_supports_width(int nw);
+size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch);
+hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                       int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
 size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef);
