@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--visited-slots", type=int, default=0)
     ap.add_argument("--lanes-per-row", type=int, default=0)
     ap.add_argument("--table-format", type=int, default=0)
+    ap.add_argument("--gpu-build", action="store_true",
+                    help="also build the graph on the GPU (qv_build_graph), time it and search it")
     ap.add_argument("--cold-host", action="store_true",
                     help="keep the float32 vectors in pinned host memory (rerank reads them over PCIe)")
     ap.add_argument("--no-scan", action="store_true", help="skip the brute-force code scan / overlap probe")
@@ -210,6 +212,33 @@ def main() -> int:
             f"{scan['roofline']['frac']:.2f} of VALU peak; top-10 overlap code vs exact {overlap:.3f}; "
             f"beam search finds {scan['graph_search_finds_code_top10']:.3f} of the code-space top-10")
 
+    # graph construction on the GPU (same reading as the oracle's orc_build_graph), timed, then searched
+    gpu_build = None
+    if args.gpu_build:
+        adj_g = qv.build_graph(codes, w.d, w.R, w.L, w.alpha, entry)      # warm-up (first launches, allocator)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        adj_g = qv.build_graph(codes, w.d, w.R, w.L, w.alpha, entry)
+        torch.cuda.synchronize()
+        t_gb = time.perf_counter() - t0
+        index_g = qv.Index(adj_g, codes, xd, entry)
+        og = qv.search(index_g, qd, k, ef, workspace=ws)
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(5):
+            og = qv.search(index_g, qd, k, ef, workspace=ws)
+        g1.record()
+        torch.cuda.synchronize()
+        rec_g = float(np.mean([len(set(a.tolist()) & set(b.tolist())) for a, b in zip(qv.to_numpy_u32(og.ids), gt)]) / k)
+        deg_g = (qv.to_numpy_u32(adj_g) != 0xFFFFFFFF).sum(1)
+        gpu_build = {"seconds": t_gb, "nodes_per_s": w.n / t_gb, "mean_degree": float(deg_g.mean()),
+                     "recall_at_10_on_it": rec_g, "qps_on_it": w.nq / (g0.elapsed_time(g1) / 5 * 1e-3),
+                     "host_generator_seconds": t_graph}
+        log(f"GPU graph construction: {t_gb:.2f} s ({w.n / t_gb / 1e3:.0f} k nodes/s), mean degree {deg_g.mean():.1f}; "
+            f"search on it: recall {rec_g:.4f}, {gpu_build['qps_on_it']:.0f} QPS")
+        del index_g, adj_g
+
     # CPU oracle on a bounded sample of the same queries, all host threads
     cpu = None
     parity = None
@@ -275,6 +304,7 @@ def main() -> int:
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},
         "cpu_baseline": cpu,
         "bq_scan": scan,
+        "gpu_graph_build": gpu_build,
     }
     print(json.dumps(line), flush=True)
     return 0
