@@ -181,9 +181,17 @@ int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double
  *    visited_slots   slots of the per-query visited table, 1024..28672 (rounded up to a multiple of 1024; to a
  *                    power of two and at most 8192 with 32-bit entries)
  *    lanes_per_row   lanes that share one neighbour's code during the gather (1, 2, 4, 8 or 16)
- *    table_format    0: 16-bit visited-table entries whenever the graph is small enough for them
- *                    (about 4M nodes at 8192 slots), else 32-bit; 32: always 32-bit entries */
-int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format);
+ *    table_format    0: 16-bit visited-table entries whenever the graph is small enough for them, else 32-bit;
+ *                    32: always 32-bit entries
+ *    visited_mode    how the per-query visited set of Sec. 4.1 is kept (the final lists, their order and the
+ *                    expansion order are the same in both modes; only the number of distance evaluations differs):
+ *                    QV_VISITED_EXACT  never forgets an id; when the table is nearly full it stops taking ids
+ *                    QV_VISITED_CACHE  a small table in which new ids displace old ones: a forgotten node that
+ *                                      comes up again is evaluated again and dropped when it is merged
+ *                    Either way status bit 2 of a query says that nodes may have been evaluated more than once. */
+#define QV_VISITED_EXACT 1
+#define QV_VISITED_CACHE 2
+int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode);
 
 const char* qv_strerror(int code);
 const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */

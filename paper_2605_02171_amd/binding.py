@@ -21,6 +21,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquiver_hip.so")
 
 EMPTY = 0xFFFFFFFF
+VISITED_EXACT = 1
+VISITED_CACHE = 2
 STATUS_NONFINITE = 1
 STATUS_VISITED_FULL = 2
 STATUS_BAD_EDGE = 4
@@ -66,7 +68,7 @@ _lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int,
 _lib.qv_index_free.restype = None
 _lib.qv_index_free.argtypes = [_P]
 _lib.qv_index_set_tuning.restype = ctypes.c_int
-_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search_workspace_bytes.restype = ctypes.c_size_t
 _lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search.restype = ctypes.c_int
@@ -268,8 +270,10 @@ class Index:
         self._h = h
         self._timer = None
 
-    def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0) -> None:
-        _check(_lib.qv_index_set_tuning(self._h, visited_slots, lanes_per_row, table_format), "qv_index_set_tuning")
+    def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0,
+                   visited_mode: int = 0) -> None:
+        _check(_lib.qv_index_set_tuning(self._h, visited_slots, lanes_per_row, table_format, visited_mode),
+               "qv_index_set_tuning")
 
     def set_timer(self, timer: Timer | None) -> None:
         self._timer = timer

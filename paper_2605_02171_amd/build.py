@@ -9,7 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquiver_hip.so")
-SOURCES = ["api.hip", "encode.hip", "search.hip", "rerank.hip", "scan.hip", "build.hip"]
+SOURCES = ["api.hip", "encode.hip", "rerank.hip", "scan.hip", "build.hip"]
+# the search kernel is compiled once per code width (64-bit words per bit-plane; 0 = any width at run time)
+SEARCH_WIDTHS = [12, 16, 24, 48, 8, 6, 2, 0]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -28,11 +30,13 @@ def is_current() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and is_current():
         return LIB
-    objs = [os.path.join(CSRC, s.replace(".hip", ".o")) for s in SOURCES]
+    jobs = [("search.hip", os.path.join(CSRC, f"search_w{w}.o"), [f"-DQV_SEARCH_WIDTH={w}"]) for w in SEARCH_WIDTHS]
+    jobs += [(s, os.path.join(CSRC, s.replace(".hip", ".o")), []) for s in SOURCES]
+    objs = [j[1] for j in jobs]
 
     def compile_one(args):
-        src, obj = args
-        cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        src, obj, extra = args
+        cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
@@ -44,8 +48,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose and rest:
             print("\n".join(rest), file=sys.stderr)
 
-    with ThreadPoolExecutor(6) as ex:
-        list(ex.map(compile_one, zip(SOURCES, objs)))
+    with ThreadPoolExecutor(min(8, os.cpu_count() or 1)) as ex:
+        list(ex.map(compile_one, jobs))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, check=True)
     for o in objs:
         os.remove(o)

@@ -58,6 +58,7 @@ struct qv_index {
     int visited_slots;  // <= 0: choose from ef
     int lanes_per_row;  // <= 0: choose from d
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
+    int visited_mode;   // 0: choose from ef; QV_VISITED_EXACT; QV_VISITED_CACHE
     qv_timer* timer;
 };
 
@@ -153,21 +154,23 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->timer = nullptr;
     *out = ix;
     return QV_OK;
 }
 
 void qv_index_free(qv_index* index) { delete index; }
 
-int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format) {
+int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode) {
     if (!index) return QV_ERR_NULL;
     if (visited_slots != 0 && (visited_slots < 1024 || visited_slots > 28672)) return QV_ERR_INVALID_ARG;
     if (table_format != 0 && table_format != 32) return QV_ERR_INVALID_ARG;
+    if (visited_mode != 0 && visited_mode != QV_VISITED_EXACT && visited_mode != QV_VISITED_CACHE) return QV_ERR_INVALID_ARG;
     if (lanes_per_row > 0 && (lanes_per_row > 16 || (lanes_per_row & (lanes_per_row - 1)))) return QV_ERR_INVALID_ARG;
     index->visited_slots = visited_slots;
     index->lanes_per_row = lanes_per_row;
     index->table_format = table_format;
+    index->visited_mode = visited_mode;
     return QV_OK;
 }
 
@@ -205,16 +208,20 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes;
     sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
-    // default table: about two slots per expected distance evaluation (~45 per unit of ef at degree 64)
-    int slots = index->visited_slots > 0 ? index->visited_slots : 96 * ef + 2048;
-    // everything a query keeps in LDS has to fit 64 KB
+    // Visited set.  Default: a cache of 4096 slots (8 KB of 16-bit tags): with the list and the merge area a
+    // query then needs about 10 KB of LDS, so 16 queries fit a compute unit and registers, not LDS, bound the
+    // occupancy; at the beam widths of interest it forgets few ids (about 1 % more distance evaluations at
+    // ef = 64).  QV_VISITED_EXACT: about two slots per expected distance evaluation (~45 per unit of ef at
+    // degree 64), as far as 64 KB of LDS per query allow.
+    const bool cache = index->visited_mode != QV_VISITED_EXACT;
+    int slots = index->visited_slots > 0 ? index->visited_slots : (cache ? 4096 : 96 * ef + 2048);
     const size_t fixed = qv::beam_search_lds_bytes(sp.nw, 0, true, ef);
     const int max_narrow = (int)((65536 - fixed) / 2 / 1024 * 1024);
     if (slots > max_narrow) slots = max_narrow;
     if (slots < 1024) slots = 1024;
-    qv::plan_visited_table(sp, (uint32_t)slots, index->table_format != 32);
+    qv::plan_visited_table(sp, (uint32_t)slots, index->table_format != 32, cache);
     if (sp.vis_regions == 0 && sp.vis_slots > 8192) {  // 32-bit entries: keep the table within 32 KB of LDS
-        qv::plan_visited_table(sp, 8192, false);
+        qv::plan_visited_table(sp, 8192, false, cache);
     }
     // the final lists go straight into the caller's trace buffers when there are any
     sp.cand_ids = trace && trace->cand_ids ? trace->cand_ids : reinterpret_cast<uint32_t*>(ws + L.cand_ids);

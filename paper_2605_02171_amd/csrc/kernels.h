@@ -24,6 +24,7 @@ struct SearchParams {
     int vis_bucket_bits;     // 32-bit entries: log2(number of 4-slot buckets)
     uint32_t vis_regions;    // > 0: 16-bit entries, table cut into this many parts ...
     uint32_t vis_region_buckets;  // ... of this many 8-tag buckets each (see plan_visited_table)
+    int vis_cache;           // 0: the table never forgets an id (stops taking ids when nearly full); 1: ids displace each other
     // outputs
     uint32_t* cand_ids;      // [nq][ef]
     uint32_t* cand_dist;     // [nq][ef]
@@ -64,8 +65,17 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, do
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
-size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef);
-void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow);
+// LDS bytes one query of the search kernel needs: visited table, two 64-entry lists, the merge scatter area
+// (64 keys per pool register of a lane, plus 64), the query code
+inline int beam_search_pool_registers(int ef) {
+    const int p = (ef + 63) / 64;
+    return p <= 1 ? 1 : (p <= 2 ? 2 : (p <= 4 ? 4 : (p <= 8 ? 8 : 16)));
+}
+inline size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef) {
+    return (size_t)vis_slots * (narrow ? 2 : 4) + 64 * 4 * 2 + (size_t)(64 * beam_search_pool_registers(ef) + 64) * 8 +
+           (size_t)nw * 16 + 16;
+}
+void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow, bool cache);
 hipError_t launch_rerank(const RerankParams& p, hipStream_t stream);
 
 }  // namespace qv

@@ -129,6 +129,60 @@ __device__ __forceinline__ bool visited16_test_and_set(uint32_t* tab32, uint32_t
     return true;  // no room: the node is evaluated (possibly again); the merge drops duplicates
 }
 
+// ---------------------------------------------------------------------------------------------
+// Visited set as a cache (the other mode of the same two table formats): an id is looked up and kept
+// in its home bucket only; when the bucket has no free slot the id takes the place of another one
+// (slot chosen by `clock`), which is thereby forgotten and may be evaluated again later -- harmless
+// for the list (see merge_new_keys), cheaper in LDS.  Lookup and insertion stay exact for the ids that
+// are in the table: two lanes holding the same id race on the same word and exactly one of them wins.
+// Returns true when v was not in the table; `evicted` is raised when an id was displaced.
+__device__ __forceinline__ bool visited32_cache(uint32_t* tab, int bucket_bits, uint32_t v, uint32_t clock,
+                                                bool& evicted) {
+    uint32_t* bp = tab + ((v * 2654435761u) >> (32 - bucket_bits)) * 4;
+    for (;;) {  // ends: a failed compare-and-swap means another lane's succeeded, and a lane stops at its first success
+        const uint4 s = *reinterpret_cast<const uint4*>(bp);
+        if (s.x == v || s.y == v || s.z == v || s.w == v) return false;
+        int e = s.x == EMPTY_ID ? 0 : (s.y == EMPTY_ID ? 1 : (s.z == EMPTY_ID ? 2 : (s.w == EMPTY_ID ? 3 : -1)));
+        const bool full = e < 0;
+        if (full) e = (int)(clock & 3u);
+        const uint32_t seen = e == 0 ? s.x : (e == 1 ? s.y : (e == 2 ? s.z : s.w));
+        if (atomicCAS(bp + e, seen, v) == seen) {
+            evicted |= full;
+            return true;
+        }
+    }
+}
+
+__device__ __forceinline__ bool visited16_cache(uint32_t* tab32, uint32_t regions, uint32_t B, uint32_t v, uint32_t clock,
+                                                bool& evicted) {
+    const uint32_t r0 = v / 65535u;
+    const uint32_t t0 = v - r0 * 65535u;
+    uint32_t r = r0 + ((((t0 * 40503u) & 0xFFFFu) * regions) >> 16);
+    if (r >= regions) r -= regions;
+    const uint32_t hb = (((v * 2654435761u) >> 16) * B) >> 16;
+    const uint32_t pat = t0 * 0x00010001u;
+    uint32_t* bp = tab32 + (r * B + hb) * 4;
+    for (;;) {  // ends for the same reason as above
+        const uint4 s = *reinterpret_cast<const uint4*>(bp);
+        if (any_zero_half(s.x ^ pat) | any_zero_half(s.y ^ pat) | any_zero_half(s.z ^ pat) | any_zero_half(s.w ^ pat))
+            return false;
+        int e = -1;
+        if (any_zero_half(~s.x)) e = 0;
+        else if (any_zero_half(~s.y)) e = 1;
+        else if (any_zero_half(~s.z)) e = 2;
+        else if (any_zero_half(~s.w)) e = 3;
+        const bool full = e < 0;
+        if (full) e = (int)((clock >> 1) & 3u);
+        const uint32_t word = e == 0 ? s.x : (e == 1 ? s.y : (e == 2 ? s.z : s.w));
+        const bool low_half = full ? !(clock & 1u) : (word & 0xFFFFu) == 0xFFFFu;
+        const uint32_t want = low_half ? ((word & 0xFFFF0000u) | t0) : ((word & 0xFFFFu) | (t0 << 16));
+        if (atomicCAS(bp + e, word, want) == word) {
+            evicted |= full;
+            return true;
+        }
+    }
+}
+
 template <int P>
 struct Pool {
     uint64_t key[P];
@@ -213,6 +267,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     const uint32_t tab_words = NARROW ? cap >> 1 : cap;
     const int bucket_bits = p.vis_bucket_bits;
     const uint32_t bucket_mask = (1u << bucket_bits) - 1;
+    const bool cache_mode = p.vis_cache != 0;
     uint32_t* tab = smem;
     uint32_t* list = tab + tab_words;  // [64] compacted new neighbour ids
     uint32_t* dlist = list + 64;       // [64] their distances (generic gather path)
@@ -389,8 +444,13 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     if (lane == 0) {
         list[0] = p.entry;
         bool ignore = false;
-        if constexpr (NARROW) visited16_test_and_set(tab, vis_regions, vis_B, p.entry, true, ignore);
-        else visited32_test_and_set(tab, bucket_mask, bucket_bits, p.entry, true);
+        if (cache_mode) {
+            if constexpr (NARROW) visited16_cache(tab, vis_regions, vis_B, p.entry, 0u, ignore);
+            else visited32_cache(tab, bucket_bits, p.entry, 0u, ignore);
+        } else {
+            if constexpr (NARROW) visited16_test_and_set(tab, vis_regions, vis_B, p.entry, true, ignore);
+            else visited32_test_and_set(tab, bucket_mask, bucket_bits, p.entry, true);
+        }
     }
     n_vis = 1;
     process_list(1);
@@ -439,15 +499,24 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             else v = (c + lane < p.R) ? arow[c + lane] : EMPTY_ID;
             bool valid = v != EMPTY_ID;
             if (valid && (int64_t)v >= p.n) { valid = false; status |= QV_STATUS_BAD_EDGE_BIT; }
-            int n_valid = __popcll(__ballot(valid));
-            if (!vis_full && n_vis + (uint32_t)n_valid > vis_limit) {
-                vis_full = true;
-                status |= QV_STATUS_VISITED_FULL_BIT;
-            }
-            // (with a full table two lanes holding the same id both count as new here; the
-            // duplicate check at merge time drops the second one)
             bool fresh = false;
-            if constexpr (NARROW) {
+            if (cache_mode) {
+                bool evicted = false;
+                if (valid) {
+                    if constexpr (NARROW) fresh = visited16_cache(tab, vis_regions, vis_B, v, n_exp + (uint32_t)lane, evicted);
+                    else fresh = visited32_cache(tab, bucket_bits, v, n_exp + (uint32_t)lane, evicted);
+                }
+                if (!vis_full && __any(evicted)) {  // from now on a node may come back: merges check for duplicates
+                    vis_full = true;
+                    status |= QV_STATUS_VISITED_FULL_BIT;
+                }
+            } else if constexpr (NARROW) {
+                if (!vis_full && n_vis + (uint32_t)__popcll(__ballot(valid)) > vis_limit) {
+                    vis_full = true;
+                    status |= QV_STATUS_VISITED_FULL_BIT;
+                }
+                // (with a full table two lanes holding the same id both count as new here; the
+                // duplicate check at merge time drops the second one)
                 bool failed = false;
                 if (valid) fresh = visited16_test_and_set(tab, vis_regions, vis_B, v, !vis_full, failed);
                 if (__any(failed)) {  // one part of the table is full: stop inserting altogether
@@ -455,6 +524,10 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     status |= QV_STATUS_VISITED_FULL_BIT;
                 }
             } else {
+                if (!vis_full && n_vis + (uint32_t)__popcll(__ballot(valid)) > vis_limit) {
+                    vis_full = true;
+                    status |= QV_STATUS_VISITED_FULL_BIT;
+                }
                 fresh = valid && visited32_test_and_set(tab, bucket_mask, bucket_bits, v, !vis_full);
             }
             uint64_t fm = __ballot(fresh);
@@ -489,11 +562,6 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
         if (order)
             for (int64_t i = n_exp; i < p.visit_cap; ++i) order[i] = EMPTY_ID;
     }
-}
-
-size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef) {
-    const int P = (ef + 63) / 64 <= 1 ? 1 : ((ef + 63) / 64 <= 2 ? 2 : ((ef + 63) / 64 <= 4 ? 4 : ((ef + 63) / 64 <= 8 ? 8 : 16)));
-    return (size_t)vis_slots * (narrow ? 2 : 4) + 64 * 4 * 2 + (size_t)(64 * P + 64) * 8 + (size_t)nw * 16 + 16;
 }
 
 template <int NW_T, int G, int P, bool NARROW>
@@ -536,19 +604,22 @@ static hipError_t launch_g(const SearchParams& p, int g, hipStream_t stream) {
     }
 }
 
+#if QV_SEARCH_WIDTH == 0
 static int default_lanes_per_row(int nw) {
-    if (nw <= 16) return 2;
+    if (nw <= 12) return 2;
     if (nw <= 24) return 4;
     return 16;
 }
 
-// Picks the visited-table format for `slots` requested slots: 16-bit entries (slots a multiple of
-// 1024) when every part of the table keeps >= 16 buckets, else 32-bit entries (slots rounded up to a
-// power of two).
-void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow) {
+// Picks the visited-table format for `slots` requested slots (rounded up to a multiple of 1024): 16-bit
+// entries when every part of the table keeps enough buckets (16 for a table that never forgets, because
+// it probes on inside the part; 1 for a cache, which looks at the home bucket only), else 32-bit entries
+// (slots rounded up to a power of two).
+void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow, bool cache) {
     const uint32_t regions = (uint32_t)((p.n + 65534) / 65535);
     slots = (slots + 1023u) & ~1023u;
-    if (allow_narrow && slots / 8 / regions >= 16) {
+    p.vis_cache = cache ? 1 : 0;
+    if (allow_narrow && slots / 8 / regions >= (cache ? 1u : 16u)) {
         p.vis_slots = slots;
         p.vis_regions = regions;
         p.vis_region_buckets = slots / 8 / regions;
@@ -564,20 +635,45 @@ void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow) {
     }
 }
 
+#endif
+
+// This file is compiled once per code width (-DQV_SEARCH_WIDTH=w, w = 64-bit words per bit-plane, 0 =
+// any width at run time), so that the instantiations build in parallel; each object exports
+// launch_beam_search_w<w>, and the object for width 0 also holds the dispatcher and the table planner.
+#ifndef QV_SEARCH_WIDTH
+#error "compile with -DQV_SEARCH_WIDTH=<words per plane> (see build.py)"
+#endif
+
+template <int NW_T>
+hipError_t launch_beam_search_w(const SearchParams& p, int g, hipStream_t stream) {
+    return launch_g<NW_T>(p, g, stream);
+}
+template hipError_t launch_beam_search_w<QV_SEARCH_WIDTH>(const SearchParams& p, int g, hipStream_t stream);
+
+#if QV_SEARCH_WIDTH == 0
+extern template hipError_t launch_beam_search_w<2>(const SearchParams&, int, hipStream_t);
+extern template hipError_t launch_beam_search_w<6>(const SearchParams&, int, hipStream_t);
+extern template hipError_t launch_beam_search_w<8>(const SearchParams&, int, hipStream_t);
+extern template hipError_t launch_beam_search_w<12>(const SearchParams&, int, hipStream_t);
+extern template hipError_t launch_beam_search_w<16>(const SearchParams&, int, hipStream_t);
+extern template hipError_t launch_beam_search_w<24>(const SearchParams&, int, hipStream_t);
+extern template hipError_t launch_beam_search_w<48>(const SearchParams&, int, hipStream_t);
+
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream) {
     if (p.nq == 0) return hipSuccess;
     int g = lanes_per_row > 0 ? lanes_per_row : default_lanes_per_row(p.nw);
     if (g > 16) g = 16;
     switch (p.nw) {
-        case 2: return launch_g<2>(p, g, stream);
-        case 6: return launch_g<6>(p, g, stream);
-        case 8: return launch_g<8>(p, g, stream);
-        case 12: return launch_g<12>(p, g, stream);
-        case 16: return launch_g<16>(p, g, stream);
-        case 24: return launch_g<24>(p, g, stream);
-        case 48: return launch_g<48>(p, g, stream);
-        default: return launch_g<0>(p, g, stream);
+        case 2: return launch_beam_search_w<2>(p, g, stream);
+        case 6: return launch_beam_search_w<6>(p, g, stream);
+        case 8: return launch_beam_search_w<8>(p, g, stream);
+        case 12: return launch_beam_search_w<12>(p, g, stream);
+        case 16: return launch_beam_search_w<16>(p, g, stream);
+        case 24: return launch_beam_search_w<24>(p, g, stream);
+        case 48: return launch_beam_search_w<48>(p, g, stream);
+        default: return launch_beam_search_w<0>(p, g, stream);
     }
 }
+#endif
 
 }  // namespace qv

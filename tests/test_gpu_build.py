@@ -68,21 +68,26 @@ def test_build_hub_takes_only_the_nearest_new_candidates(qv):
 
 
 def test_build_then_search_end_to_end(qv):
-    # a graph built on the GPU serves the search path like any other input graph
-    w = datagen.scaled("H2", n=20_000, nq=100)
+    # a graph built on the GPU serves the search path like any other input graph: searching it returns, bit for
+    # bit, what the oracle returns on the graph the oracle built (the rows are equal as sets and the search does
+    # not depend on the order inside a row)
+    w = datagen.scaled("H2", n=2_500, nq=100, d=128)
     x, q = datagen.make_base(w), datagen.make_queries(w)
+    ocodes = oracle.encode(x, threads=8)
+    util.note("end to end: oracle builds 2500 x 128, R=32, L=64")
+    oadj = oracle.build_graph(ocodes, w.d, 32, 64, 1.2, 0)
+    ref = oracle.search(q, oadj, ocodes, x, 0, 10, 64, threads=8)
     xd = torch.from_numpy(x).cuda()
     codes = qv.encode(xd)
     adj = qv.build_graph(codes, w.d, 32, 64, 1.2, 0)
     index = qv.Index(adj, codes, xd, 0)
     out = qv.search(index, torch.from_numpy(q).cuda(), 10, 64, trace=True)
     torch.cuda.synchronize()
-    adj_h = qv.to_numpy_u32(adj)
-    ref = oracle.search(q, adj_h, qv.to_numpy_u64(codes), x, 0, 10, 64, threads=8)
     assert (qv.to_numpy_u32(out.cand_ids) == ref.cand_ids).all()
+    assert (qv.to_numpy_u32(out.cand_dist) == ref.cand_dist).all()
     exact = oracle.cosine_topk(x, q, 10, threads=8)
-    assert util.recall_at_k(qv.to_numpy_u32(out.ids), exact) > 0.8
-    deg = (adj_h != E).sum(1)
+    assert util.recall_at_k(qv.to_numpy_u32(out.ids), exact) > 0.7
+    deg = (qv.to_numpy_u32(adj) != E).sum(1)
     assert deg.max() <= 32 and deg.min() >= 1
 
 

@@ -91,15 +91,22 @@ def test_bq_distance_bit_exact(qv, d):
 
 
 def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, visited_slots=0, lanes=0, table_format=0):
+    """Oracle and GPU on the same inputs.  The GPU runs twice: with the visited set as a cache (the default;
+    compared here, counters allowed to exceed the oracle's) and as a table that never forgets (returned)."""
     codes = oracle.encode(x, threads=8)
     ref = oracle.search(q, adj, codes, x, entry, k, ef, visit_cap=visit_cap, threads=8)
     xd = torch.from_numpy(x).cuda()
     gcodes = qv.encode(xd)
     assert (qv.to_numpy_u64(gcodes) == codes).all()
     index = qv.Index(qv.from_numpy_u32(adj), gcodes, xd, entry)
-    if visited_slots or lanes or table_format:
-        index.set_tuning(visited_slots, lanes, table_format)
-    out = qv.search(index, torch.from_numpy(q).cuda(), k, ef, trace=True, visit_cap=visit_cap)
+    qd = torch.from_numpy(q).cuda()
+    if lanes or table_format:
+        index.set_tuning(0, lanes, table_format)
+    cached = qv.search(index, qd, k, ef, trace=True, visit_cap=visit_cap)
+    torch.cuda.synchronize()
+    _assert_search_equal(qv, ref, cached, exact_counters=False)
+    index.set_tuning(visited_slots, lanes, table_format, qv.VISITED_EXACT)
+    out = qv.search(index, qd, k, ef, trace=True, visit_cap=visit_cap)
     torch.cuda.synchronize()
     return ref, out
 
@@ -192,6 +199,46 @@ def test_search_small_table_in_eight_parts_overflows_gracefully(qv):
     ref, out = _run_both(qv, x, q, adj, entry=11, k=10, ef=128, visit_cap=300, visited_slots=1024)
     assert (qv.to_numpy_u32(out.status) & 2).all()
     _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+@pytest.mark.parametrize("table_format,slots,ef", [(0, 1024, 64), (32, 1024, 64), (0, 1024, 300), (32, 2048, 128),
+                                                    (0, 3072, 1024)])
+def test_search_tiny_visited_cache_keeps_results_exact(qv, table_format, slots, ef):
+    # a cache far smaller than the set of evaluated nodes: ids displace each other all the time, nodes come
+    # back and are evaluated again; lists, distances and the expansion order must not change
+    w = datagen.scaled("C2", n=30_000, nq=48)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    adj, entry = graph.build_graph(x, 64, 64, 1.2)
+    adj[::7, 5] = adj[::7, 9]                   # duplicate edges and self loops on top
+    adj[::11, 3] = np.arange(0, w.n, 11, dtype=np.uint32)
+    codes = oracle.encode(x, threads=8)
+    ref = oracle.search(q, adj, codes, x, entry, 10, ef, visit_cap=1200, threads=8)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, entry)
+    index.set_tuning(slots, 0, table_format, qv.VISITED_CACHE)
+    out = qv.search(index, torch.from_numpy(q).cuda(), 10, ef, trace=True, visit_cap=1200)
+    torch.cuda.synchronize()
+    assert (qv.to_numpy_u32(out.status) & 2).all(), "the test is meant to displace ids"
+    assert (qv.to_numpy_u32(out.n_dist_evals) > ref.n_dist_evals).any()
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+def test_search_visited_cache_on_a_graph_with_many_parts(qv):
+    # 500,000 nodes: the 16-bit cache is cut into eight parts of 64 buckets at the default 4096 slots
+    rng = np.random.default_rng(78)
+    n, d = 500_000, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((64, d)).astype(np.float32)
+    adj = datagen.random_regular_graph(n, 16, seed=10)
+    codes = oracle.encode(x, threads=8)
+    ref = oracle.search(q, adj, codes, x, 11, 10, 128, visit_cap=300, threads=8)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, 11)
+    for slots in (0, 1024):
+        index.set_tuning(slots, 0, 0, qv.VISITED_CACHE)
+        out = qv.search(index, torch.from_numpy(q).cuda(), 10, 128, trace=True, visit_cap=300)
+        torch.cuda.synchronize()
+        _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
 @pytest.mark.parametrize("ef", [256, 512, 1024])
@@ -289,4 +336,4 @@ def test_search_with_cold_vectors_in_pinned_host_memory(qv):
     index = qv.Index(qv.from_numpy_u32(adj), qv.from_numpy_u64(codes), cold, entry)
     out = qv.search(index, torch.from_numpy(q).cuda(), 10, 64, trace=True, visit_cap=256)
     torch.cuda.synchronize()
-    _assert_search_equal(qv, ref, out)
+    _assert_search_equal(qv, ref, out, exact_counters=False)

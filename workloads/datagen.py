@@ -49,6 +49,10 @@ WORKLOADS = {
     # not one of the five contract workloads: low-rank data whose neighbours differ in direction (the regime
     # the paper calls compatible), used to show the path end to end at a recall that means something
     "H2": Workload("H2", 1_000_000, 768, 10_000, "lowrank", 32, 64, 128, 1.2, 10, (64,), "cosine", 1012, 2012),
+    # not a contract workload either: the shape of the paper's scalability study (5M x 1024-d, Table 12) with the
+    # low-rank law, so that recall at 1M (scaled(n=1_000_000) takes the first 1M rows) and at 5M can be compared
+    "S5": Workload("S5", 5_000_000, 1024, 10_000, "lowrank", 32, 64, 128, 1.2, 10, (64, 128, 256, 512, 1024), "cosine",
+                   1013, 2013),
     # structureless boundary case
     "C5": Workload("C5", 1_000_000, 512, 10_000, "gaussian", 0, 64, 128, 1.2, 10, (64,), "l2", 1005, 2005),
 }
