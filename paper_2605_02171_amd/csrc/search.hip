@@ -254,6 +254,77 @@ __device__ __forceinline__ void merge_new_keys(Pool<P>& pool, uint64_t mine, int
     pool.size = new_size;
 }
 
+// The same merge for pools of eight and more registers per lane, where a loop over the new keys that
+// touches every pool register is the dominant cost of an expansion.  skeys[0..pool.size) still holds
+// the pool as the previous merge left it (sorted; only `expanded` bits may be stale, and they are
+// ignored here), so every lane finds the rank of its own key among the pool keys, and whether the
+// pool already holds it, by a binary search in LDS, all lanes at once.  What is left for the loop over
+// the new keys is wave-uniform data: their pool ranks (a pool entry e moves up by the number of new
+// keys whose rank is <= e) and their order among themselves.
+template <int P>
+__device__ __forceinline__ void merge_new_keys_wide(Pool<P>& pool, uint64_t mine, int ef, int lane, bool check_dup,
+                                                    uint64_t* skeys) {
+    uint64_t worst = KEY_NONE;
+#pragma unroll
+    for (int r = 0; r < P; ++r)
+        if (r == ((ef - 1) >> 6)) worst = readlane64(pool.key[r], (ef - 1) & 63);
+    bool cand = mine < worst;
+    uint64_t qual = __ballot(cand);
+    if (!qual) return;
+
+    const int n = pool.size;
+    const uint64_t k1 = mine >> 1;
+    uint32_t rank = 0;  // pool keys whose (dist, id) is below mine
+    if (cand) {
+        for (int step = n > 0 ? 1 << (31 - __clz(n)) : 0; step > 0; step >>= 1) {
+            const uint32_t t = rank + (uint32_t)step;
+            if (t <= (uint32_t)n && (skeys[t - 1] >> 1) < k1) rank = t;
+        }
+        if (check_dup && rank < (uint32_t)n && (skeys[rank] >> 1) == k1) cand = false;  // the pool holds it already
+    }
+    if (check_dup) {
+        qual = __ballot(cand);
+        if (!qual) return;
+    }
+
+    uint32_t up[P];
+#pragma unroll
+    for (int r = 0; r < P; ++r) up[r] = 0;
+    uint32_t my_pos = rank;
+    uint64_t twins = 0;   // lanes whose key a lower lane holds as well
+    uint64_t scan = qual;
+    while (scan) {
+        const int j = __ffsll((unsigned long long)scan) - 1;
+        scan &= scan - 1;
+        if ((twins >> j) & 1ull) {
+            qual &= ~(1ull << j);
+            continue;
+        }
+        const uint64_t nk = readlane64(mine, j);
+        const uint32_t rj = (uint32_t)__builtin_amdgcn_readlane((int)rank, j);
+        if (check_dup) twins |= __ballot(cand && lane > j && mine == nk);
+#pragma unroll
+        for (int r = 0; r < P; ++r) up[r] += (uint32_t)(r * 64 + lane) >= rj ? 1u : 0u;
+        my_pos += (cand && nk < mine) ? 1u : 0u;
+    }
+    const bool is_new = (qual >> lane) & 1ull;
+    const int new_size = min(ef, n + (int)__popcll(qual));
+    wave_sync();
+#pragma unroll
+    for (int r = 0; r < P; ++r) {
+        const uint32_t np = (uint32_t)(r * 64 + lane) + up[r];
+        if (pool.key[r] != KEY_NONE && np < (uint32_t)ef) skeys[np] = pool.key[r];
+    }
+    if (is_new && my_pos < (uint32_t)ef) skeys[my_pos] = mine;
+    wave_sync();
+#pragma unroll
+    for (int r = 0; r < P; ++r) {
+        const int e = r * 64 + lane;
+        pool.key[r] = e < new_size ? skeys[e] : KEY_NONE;
+    }
+    pool.size = new_size;
+}
+
 template <int NW_T, int G, int P, bool NARROW>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
@@ -437,7 +508,8 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             if (lane < m) mine = ((uint64_t)dlist[lane] << 33) | ((uint64_t)list[lane] << 1);
         }
         n_eval += (uint32_t)m;
-        merge_new_keys<P>(pool, mine, ef, lane, vis_full, skeys);
+        if constexpr (P >= 8) merge_new_keys_wide<P>(pool, mine, ef, lane, vis_full, skeys);
+        else merge_new_keys<P>(pool, mine, ef, lane, vis_full, skeys);
     };
 
     // the entry node
