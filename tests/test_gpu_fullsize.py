@@ -135,3 +135,9 @@ def test_full_size_low_rank_extra_workload_has_meaningful_recall(qv):
     # not one of the five contract workloads: data in the regime the paper calls compatible, where
     # Recall@10 is high, so equality of recall with the oracle is a sharper statement
     _full_case(qv, "H2", efs=(64,), n_sample=1000, L=64)
+
+
+def test_full_size_5m_nodes_1024d(qv):
+    # the shape of the paper's scalability study (Table 12): 5M vectors, 1024-d; ids beyond 2^22 and a visited
+    # table cut into 77 parts
+    _full_case(qv, "S5", efs=(64,), n_sample=300, L=64)
