@@ -33,6 +33,20 @@
  *   - rerank: all entries of the final list, cosine accumulated in double,
  *     rounded to float once, ordered by (score descending, id ascending).
  *
+ *
+ * The two alternative encodings of the paper's ablation (Sec. 5.4 "Encoding
+ * Ablation", Table 10) are here as well, selected by an `enc` argument of the
+ * *_enc entry points (0 = Sign-Magnitude, the default everywhere else):
+ *   - enc 1, "1-bit sign": pos_i only, distance = number of differing signs.
+ *   - enc 2, "2-bit SQ": every dimension falls into one of four equal-width
+ *     buckets, distance = sum of |level_a - level_b| (L1).  The paper does not
+ *     say over which range; the reading here is the vector's own value range
+ *     [min_i x_i, max_i x_i] (so no training data is involved, like tau):
+ *     level = number of k in {1,2,3} with 4*(x - min) >= k*(max - min), every
+ *     product and difference evaluated in IEEE double in exactly this form; a
+ *     constant vector gets level 3 everywhere.  Stored as two bit-planes, low
+ *     bit of the level first, same packing as above.
+ *
  * Parity pins for every function here live in tests/test_oracle_*.py.
  */
 #include <math.h>
@@ -188,6 +202,103 @@ int orc_sm_distance_pairs(const uint64_t *codes_a, const int64_t *ia, const uint
 }
 
 /* ------------------------------------------------------------------ */
+/* Ablation encodings (Sec. 5.4, Table 10).                            */
+/* ------------------------------------------------------------------ */
+#define ORC_ENC_SM 0
+#define ORC_ENC_SIGN1 1
+#define ORC_ENC_SQ2 2
+
+int orc_code_words_enc(int d, int enc) {
+    if (d < 1 || enc < 0 || enc > 2) return 0;
+    return (enc == ORC_ENC_SIGN1 ? 1 : 2) * ((d + 63) / 64);
+}
+
+static int encode_sign1(const float *x, int d, uint64_t *code) {
+    int W = (d + 63) / 64;
+    for (int w = 0; w < W; ++w) code[w] = 0;
+    for (int i = 0; i < d; ++i) {
+        if (!isfinite(x[i])) return ORC_ERR_NONFINITE;
+        if (x[i] > 0.0f) code[i / 64] |= (uint64_t)1 << (i % 64);
+    }
+    return ORC_OK;
+}
+
+static int sq2_level(float x, float mn, float mx) {
+    double width = (double)mx - (double)mn;
+    double t = ((double)x - (double)mn) * 4.0;
+    int level = 0;
+    if (t >= width) level++;
+    if (t >= 2.0 * width) level++;
+    if (t >= 3.0 * width) level++;
+    return level;
+}
+
+static int encode_sq2(const float *x, int d, uint64_t *code) {
+    int W = (d + 63) / 64;
+    for (int w = 0; w < 2 * W; ++w) code[w] = 0;
+    float mn = x[0], mx = x[0];
+    for (int i = 0; i < d; ++i) {
+        if (!isfinite(x[i])) return ORC_ERR_NONFINITE;
+        if (x[i] < mn) mn = x[i];
+        if (x[i] > mx) mx = x[i];
+    }
+    for (int i = 0; i < d; ++i) {
+        int level = sq2_level(x[i], mn, mx);
+        if (level & 1) code[i / 64] |= (uint64_t)1 << (i % 64);
+        if (level & 2) code[W + i / 64] |= (uint64_t)1 << (i % 64);
+    }
+    return ORC_OK;
+}
+
+static int encode_vec(int enc, const float *x, int d, uint64_t *code) {
+    if (enc == ORC_ENC_SIGN1) return encode_sign1(x, d, code);
+    if (enc == ORC_ENC_SQ2) return encode_sq2(x, d, code);
+    return encode_one(x, d, code);
+}
+
+int orc_encode_enc(const float *x, int64_t n, int d, int enc, uint64_t *codes, int threads) {
+    if (!x || !codes || n < 0 || d < 1 || enc < 0 || enc > 2) return ORC_ERR_ARG;
+    int cw = orc_code_words_enc(d, enc);
+    int rc = ORC_OK;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for schedule(static) num_threads(threads)
+    for (int64_t v = 0; v < n; ++v) {
+        int r = encode_vec(enc, x + v * (int64_t)d, d, codes + v * (int64_t)cw);
+        if (r != ORC_OK) {
+#pragma omp critical
+            rc = r;
+        }
+    }
+    return rc;
+}
+
+/* distance of two codes of the same encoding, dimension by dimension */
+uint32_t orc_distance_enc(const uint64_t *a, const uint64_t *b, int d, int enc) {
+    if (enc == ORC_ENC_SM) return orc_sm_distance(a, b, d);
+    int W = (d + 63) / 64;
+    uint32_t dist = 0;
+    for (int i = 0; i < d; ++i) {
+        if (enc == ORC_ENC_SIGN1) {
+            if (code_bit(a, i) != code_bit(b, i)) dist += 1u;
+        } else {
+            int la = code_bit(a, i) + 2 * code_bit(a + W, i);
+            int lb = code_bit(b, i) + 2 * code_bit(b + W, i);
+            dist += (uint32_t)(la > lb ? la - lb : lb - la);
+        }
+    }
+    return dist;
+}
+
+int orc_distance_pairs_enc(const uint64_t *codes_a, const int64_t *ia, const uint64_t *codes_b, const int64_t *ib,
+                           int64_t npairs, int d, int enc, uint32_t *out) {
+    if (!codes_a || !codes_b || !ia || !ib || !out || d < 1 || npairs < 0 || enc < 0 || enc > 2) return ORC_ERR_ARG;
+    int cw = orc_code_words_enc(d, enc);
+    for (int64_t p = 0; p < npairs; ++p)
+        out[p] = orc_distance_enc(codes_a + ia[p] * (int64_t)cw, codes_b + ib[p] * (int64_t)cw, d, enc);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------ */
 /* Stage 1: beam search (Sec. 3.3).                                    */
 /* ------------------------------------------------------------------ */
 typedef struct {
@@ -207,16 +318,16 @@ static int key_less(uint32_t da, uint32_t ia, uint32_t db, uint32_t ib) {
  * order: visit_cap slots (expanded ids in expansion order, rest ORC_EMPTY); may be NULL.
  * counters[0] = list length, [1] = nodes expanded, [2] = distances computed.
  */
-static int beam_search_one(const uint64_t *qcode, int64_t n, int d, int R, const uint32_t *adj,
+static int beam_search_one(int enc, const uint64_t *qcode, int64_t n, int d, int R, const uint32_t *adj,
                            const uint64_t *codes, uint32_t entry, int ef, uint8_t *visited, entry_t *pool,
                            uint32_t *touched, uint32_t *cand_id, uint32_t *cand_dist, uint32_t *order,
                            int64_t visit_cap, uint32_t *counters) {
-    int cw = orc_code_words(d);
+    int cw = orc_code_words_enc(d, enc);
     int size = 0;
     int64_t n_touched = 0;
     uint32_t n_evals = 0, n_expanded = 0;
 
-    pool[0].dist = orc_sm_distance(qcode, codes + (int64_t)entry * cw, d);
+    pool[0].dist = orc_distance_enc(qcode, codes + (int64_t)entry * cw, d, enc);
     pool[0].id = entry;
     pool[0].expanded = 0;
     size = 1;
@@ -248,7 +359,7 @@ static int beam_search_one(const uint64_t *qcode, int64_t n, int d, int R, const
             if (visited[v]) continue;
             visited[v] = 1;
             touched[n_touched++] = v;
-            uint32_t dv = orc_sm_distance(qcode, codes + (int64_t)v * cw, d);
+            uint32_t dv = orc_distance_enc(qcode, codes + (int64_t)v * cw, d, enc);
             n_evals++;
             if (size < ef || key_less(dv, v, pool[size - 1].dist, pool[size - 1].id)) {
                 int p = size < ef ? size : ef - 1; /* slot that becomes free */
@@ -343,18 +454,18 @@ int orc_rerank(const float *queries, int64_t nq, int d, const float *vecs, const
 /* Queries are independent; `threads` > 1 only spreads them over cores. */
 /* Optional outputs may be NULL.                                        */
 /* ------------------------------------------------------------------ */
-int orc_search(const float *queries, int64_t nq, int64_t n, int d, int R, const uint32_t *adj,
+int orc_search_enc(int enc, const float *queries, int64_t nq, int64_t n, int d, int R, const uint32_t *adj,
                const uint64_t *codes, const float *vecs /* NULL: skip stage 2 */, uint32_t entry, int k, int ef,
                uint32_t *ids, float *scores,             /* [nq][k], NULL if vecs NULL */
                uint32_t *cand_id, uint32_t *cand_dist,   /* [nq][ef] */
                uint32_t *counters,                       /* [nq][3] */
                uint32_t *order, int64_t visit_cap,       /* [nq][visit_cap] or NULL */
                int threads) {
-    if (!queries || !adj || !codes || !cand_id || !cand_dist || !counters) return ORC_ERR_ARG;
+    if (!queries || !adj || !codes || !cand_id || !cand_dist || !counters || enc < 0 || enc > 2) return ORC_ERR_ARG;
     if (nq < 0 || n < 1 || d < 1 || R < 1 || ef < 1 || (int64_t)entry >= n) return ORC_ERR_ARG;
     if (vecs && (k < 1 || k > ef || !ids || !scores)) return ORC_ERR_ARG;
     if (threads < 1) threads = 1;
-    int cw = orc_code_words(d);
+    int cw = orc_code_words_enc(d, enc);
     int rc = ORC_OK;
 #pragma omp parallel num_threads(threads)
     {
@@ -370,9 +481,9 @@ int orc_search(const float *queries, int64_t nq, int64_t n, int d, int R, const 
 #pragma omp for schedule(dynamic, 8)
         for (int64_t q = 0; q < nq; ++q) {
             if (!ok) continue;
-            int r = encode_one(queries + q * d, d, qcode);
+            int r = encode_vec(enc, queries + q * d, d, qcode);
             if (r == ORC_OK)
-                r = beam_search_one(qcode, n, d, R, adj, codes, entry, ef, visited, pool, touched,
+                r = beam_search_one(enc, qcode, n, d, R, adj, codes, entry, ef, visited, pool, touched,
                                     cand_id + q * ef, cand_dist + q * ef, order ? order + q * visit_cap : NULL,
                                     visit_cap, counters + q * 3);
             if (r == ORC_OK && vecs)
@@ -391,24 +502,31 @@ int orc_search(const float *queries, int64_t nq, int64_t n, int d, int R, const 
     return rc;
 }
 
+int orc_search(const float *queries, int64_t nq, int64_t n, int d, int R, const uint32_t *adj, const uint64_t *codes,
+               const float *vecs, uint32_t entry, int k, int ef, uint32_t *ids, float *scores, uint32_t *cand_id,
+               uint32_t *cand_dist, uint32_t *counters, uint32_t *order, int64_t visit_cap, int threads) {
+    return orc_search_enc(ORC_ENC_SM, queries, nq, n, d, R, adj, codes, vecs, entry, k, ef, ids, scores, cand_id, cand_dist,
+                          counters, order, visit_cap, threads);
+}
+
 /* ------------------------------------------------------------------ */
 /* Brute-force scan in code space (Sec. 6 "Practical compatibility     */
 /* test"; Sec. 5.4 Table 10 "Top-10 overlap"): for every query code    */
 /* the K base codes with the smallest (distance, id), by computing     */
 /* every distance.  ids/dist: [nq][K], ORC_EMPTY padded when n < K.    */
 /* ------------------------------------------------------------------ */
-int orc_bq_scan(const uint64_t *codes, int64_t n, int d, const uint64_t *qcodes, int64_t nq, int K, uint32_t *ids,
-                uint32_t *dist, int threads) {
-    if (!codes || !qcodes || !ids || !dist || n < 0 || nq < 0 || d < 1 || K < 1) return ORC_ERR_ARG;
+int orc_bq_scan_enc(int enc, const uint64_t *codes, int64_t n, int d, const uint64_t *qcodes, int64_t nq, int K,
+                    uint32_t *ids, uint32_t *dist, int threads) {
+    if (!codes || !qcodes || !ids || !dist || n < 0 || nq < 0 || d < 1 || K < 1 || enc < 0 || enc > 2) return ORC_ERR_ARG;
     if (threads < 1) threads = 1;
-    int cw = orc_code_words(d);
+    int cw = orc_code_words_enc(d, enc);
 #pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
     for (int64_t q = 0; q < nq; ++q) {
         uint32_t *bi = ids + q * K, *bd = dist + q * K;
         int size = 0;
         for (int j = 0; j < K; ++j) bi[j] = bd[j] = ORC_EMPTY;
         for (int64_t v = 0; v < n; ++v) {
-            uint32_t dv = orc_sm_distance(qcodes + q * cw, codes + v * cw, d);
+            uint32_t dv = orc_distance_enc(qcodes + q * cw, codes + v * cw, d, enc);
             if (size < K || key_less(dv, (uint32_t)v, bd[size - 1], bi[size - 1])) {
                 int p = size < K ? size : K - 1;
                 while (p > 0 && key_less(dv, (uint32_t)v, bd[p - 1], bi[p - 1])) {
@@ -423,6 +541,11 @@ int orc_bq_scan(const uint64_t *codes, int64_t n, int d, const uint64_t *qcodes,
         }
     }
     return ORC_OK;
+}
+
+int orc_bq_scan(const uint64_t *codes, int64_t n, int d, const uint64_t *qcodes, int64_t nq, int K, uint32_t *ids,
+                uint32_t *dist, int threads) {
+    return orc_bq_scan_enc(ORC_ENC_SM, codes, n, d, qcodes, nq, K, ids, dist, threads);
 }
 
 /* Exact float32-data top-K by cosine (double accumulation), order (score desc, id asc): the other side of the
@@ -509,13 +632,13 @@ static int cand_cmp(const void *a, const void *b) {
 }
 
 /* Algorithm 1: cand sorted by (dist to t, id), without t and without repeats; returns |selected| */
-static int select_edges(const uint64_t *codes, int cw, int d, const cand_t *cand, int n_cand, int R, double alpha,
-                        uint32_t *selected) {
+static int select_edges(int enc, const uint64_t *codes, int cw, int d, const cand_t *cand, int n_cand, int R,
+                        double alpha, uint32_t *selected) {
     int ns = 0;
     for (int i = 0; i < n_cand && ns < R; ++i) {
         int keep = 1;
         for (int j = 0; j < ns && keep; ++j) {
-            uint32_t dcs = orc_sm_distance(codes + (int64_t)cand[i].id * cw, codes + (int64_t)selected[j] * cw, d);
+            uint32_t dcs = orc_distance_enc(codes + (int64_t)cand[i].id * cw, codes + (int64_t)selected[j] * cw, d, enc);
             if (!((double)cand[i].dist <= alpha * (double)dcs)) keep = 0;
         }
         if (keep) selected[ns++] = cand[i].id;
@@ -523,11 +646,12 @@ static int select_edges(const uint64_t *codes, int cw, int d, const cand_t *cand
     return ns;
 }
 
-int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
-                    int64_t max_batch, uint32_t *adj) {
-    if (!codes || !adj || n < 1 || d < 1 || R < 1 || L < 1 || alpha < 1.0 || (int64_t)entry >= n || max_batch < 1)
+int orc_build_graph_enc(int enc, const uint64_t *codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                        int64_t max_batch, uint32_t *adj) {
+    if (!codes || !adj || n < 1 || d < 1 || R < 1 || L < 1 || alpha < 1.0 || (int64_t)entry >= n || max_batch < 1 ||
+        enc < 0 || enc > 2)
         return ORC_ERR_ARG;
-    int cw = orc_code_words(d);
+    int cw = orc_code_words_enc(d, enc);
     for (int64_t i = 0; i < n * R; ++i) adj[i] = ORC_EMPTY;
     uint8_t *visited = (uint8_t *)calloc((size_t)n, 1);
     uint32_t *touched = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n);
@@ -547,7 +671,7 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
         /* 1. searches and selections against the graph as it stands */
         for (int64_t i = 0; i < bs && rc == ORC_OK; ++i) {
             uint32_t t = (uint32_t)(done + i);
-            rc = beam_search_one(codes + (int64_t)t * cw, n, d, R, adj, codes, entry, L, visited, pool, touched, cid,
+            rc = beam_search_one(enc, codes + (int64_t)t * cw, n, d, R, adj, codes, entry, L, visited, pool, touched, cid,
                                  cds, NULL, 0, counters);
             if (rc != ORC_OK) break;
             cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)(L + R));
@@ -563,12 +687,12 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
                 int have = 0;
                 for (int k = 0; k < nc; ++k) have |= cand[k].id == v;
                 if (!have) {
-                    cand[nc].dist = orc_sm_distance(codes + (int64_t)t * cw, codes + (int64_t)v * cw, d);
+                    cand[nc].dist = orc_distance_enc(codes + (int64_t)t * cw, codes + (int64_t)v * cw, d, enc);
                     cand[nc++].id = v;
                 }
             }
             qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
-            nfwd[i] = select_edges(codes, cw, d, cand, nc, R, alpha, fwd + i * R);
+            nfwd[i] = select_edges(enc, codes, cw, d, cand, nc, R, alpha, fwd + i * R);
             free(cand);
         }
         /* 2. publish the rows of the batch */
@@ -595,7 +719,7 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
                 uint32_t v = adj[b * R + j];
                 if (v == ORC_EMPTY) continue;
                 cand[nc].id = v;
-                cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)v * cw, d);
+                cand[nc++].dist = orc_distance_enc(codes + b * cw, codes + (int64_t)v * cw, d, enc);
             }
             deg = nc;
             for (int64_t p = p0; p < p1; ++p) {
@@ -604,7 +728,7 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
                 for (int k = 0; k < deg; ++k) have |= cand[k].id == t;
                 if (have) continue;
                 cand[nc].id = t;
-                cand[nc++].dist = orc_sm_distance(codes + b * cw, codes + (int64_t)t * cw, d);
+                cand[nc++].dist = orc_distance_enc(codes + b * cw, codes + (int64_t)t * cw, d, enc);
                 n_new++;
             }
             if (n_new > ORC_MAX_NEW_IN_EDGES) { /* keep the nearest new candidates only */
@@ -622,7 +746,7 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
                 } else {
                     uint32_t *sel = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)R);
                     qsort(cand, (size_t)nc, sizeof(cand_t), cand_cmp);
-                    int ns = select_edges(codes, cw, d, cand, nc, R, alpha, sel);
+                    int ns = select_edges(enc, codes, cw, d, cand, nc, R, alpha, sel);
                     for (int j = 0; j < R; ++j) adj[b * R + j] = j < ns ? sel[j] : ORC_EMPTY;
                     free(sel);
                 }
@@ -641,4 +765,9 @@ int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, doubl
     free(cid);
     free(cds);
     return rc;
+}
+
+int orc_build_graph(const uint64_t *codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+                    int64_t max_batch, uint32_t *adj) {
+    return orc_build_graph_enc(ORC_ENC_SM, codes, n, d, R, L, alpha, entry, max_batch, adj);
 }
