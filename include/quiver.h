@@ -177,6 +177,34 @@ size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batc
 int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
                    int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The two alternative encodings of the paper's ablation (Sec. 5.4 "Encoding Ablation", Table 10), through the
+ * same path.  Every *_enc call is its namesake above with an `encoding` argument; QV_ENC_SM is the method itself.
+ *    QV_ENC_SIGN1  "1-bit sign": the sign plane alone, qv_code_words_enc(d) = ceil(d/64) words per vector;
+ *                  distance = number of differing signs.
+ *    QV_ENC_SQ2    "2-bit SQ": every dimension falls into one of four equal-width buckets, distance = sum of
+ *                  |level_a - level_b| (L1).  The paper names no range; here it is the vector's own value range:
+ *                  level = number of k in {1, 2, 3} with 4 (x - min) >= k (max - min), evaluated in IEEE double in
+ *                  this form (a constant vector has level 3 everywhere).  Two bit-planes, low bit of the level
+ *                  first, packed like the Sign-Magnitude planes.
+ * qv_index_set_encoding tells an index which encoding its `codes` are in (queries are then encoded the same way).
+ * Widths: encode, distance, scan and search take any d; qv_build_graph_enc takes d = 65..128 and 705..768 for the
+ * two ablation encodings (QV_ERR_UNSUPPORTED otherwise).  An unknown encoding is QV_ERR_INVALID_ARG (0 words from
+ * qv_code_words_enc).
+ */
+#define QV_ENC_SM 0
+#define QV_ENC_SIGN1 1
+#define QV_ENC_SQ2 2
+int qv_code_words_enc(int d, int encoding);
+int qv_encode_enc(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status, void* stream);
+int qv_bq_distance_enc(const uint64_t* codes_a, const int64_t* ia, const uint64_t* codes_b, const int64_t* ib,
+                       int64_t npairs, int d, int encoding, uint32_t* out, void* stream);
+int qv_bq_scan_enc(const uint64_t* codes, int64_t n, int d, int encoding, const uint64_t* qcodes, int64_t nq, int K,
+                   uint32_t* ids, uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream);
+int qv_build_graph_enc(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
+                       int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream);
+int qv_index_set_encoding(qv_index* index, int encoding);
+
 /* Tunables of the search kernel (defaults picked from the shape when 0).  Host only.
  *    visited_slots   slots of the per-query visited table, 1024..28672 (rounded up to a multiple of 1024; to a
  *                    power of two and at most 8192 with 32-bit entries)

@@ -23,6 +23,7 @@ LIB_PATH = os.path.join(_HERE, "libquiver_hip.so")
 EMPTY = 0xFFFFFFFF
 VISITED_EXACT = 1
 VISITED_CACHE = 2
+ENC_SM, ENC_SIGN1, ENC_SQ2 = 0, 1, 2
 STATUS_NONFINITE = 1
 STATUS_VISITED_FULL = 2
 STATUS_BAD_EDGE = 4
@@ -69,6 +70,20 @@ _lib.qv_index_free.restype = None
 _lib.qv_index_free.argtypes = [_P]
 _lib.qv_index_set_tuning.restype = ctypes.c_int
 _lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+_lib.qv_code_words_enc.restype = ctypes.c_int
+_lib.qv_code_words_enc.argtypes = [ctypes.c_int, ctypes.c_int]
+_lib.qv_encode_enc.restype = ctypes.c_int
+_lib.qv_encode_enc.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P]
+_lib.qv_bq_distance_enc.restype = ctypes.c_int
+_lib.qv_bq_distance_enc.argtypes = [_P, _P, _P, _P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P]
+_lib.qv_bq_scan_enc.restype = ctypes.c_int
+_lib.qv_bq_scan_enc.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, ctypes.c_int64, ctypes.c_int, _P, _P, _P,
+                                ctypes.c_size_t, _P]
+_lib.qv_build_graph_enc.restype = ctypes.c_int
+_lib.qv_build_graph_enc.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_double, ctypes.c_uint32, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]
+_lib.qv_index_set_encoding.restype = ctypes.c_int
+_lib.qv_index_set_encoding.argtypes = [_P, ctypes.c_int]
 _lib.qv_search_workspace_bytes.restype = ctypes.c_size_t
 _lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search.restype = ctypes.c_int
@@ -129,41 +144,42 @@ def from_numpy_u64(a: np.ndarray, device="cuda") -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).to(device)
 
 
-def code_words(d: int) -> int:
-    return _lib.qv_code_words(int(d))
+def code_words(d: int, enc: int = ENC_SM) -> int:
+    return _lib.qv_code_words_enc(int(d), int(enc))
 
 
-def encode(x: torch.Tensor, want_status: bool = False):
-    """qv_encode: float32 [n, d] on the device -> int64 [n, code_words(d)] (uint64 bit patterns)."""
+def encode(x: torch.Tensor, want_status: bool = False, enc: int = ENC_SM):
+    """qv_encode / qv_encode_enc: float32 [n, d] on the device -> int64 [n, code_words(d, enc)] (uint64 bit patterns)."""
     x = _dev(x, torch.float32, "x")
     if x.dim() != 2:
         raise ValueError("x must be [n, d]")
     n, d = x.shape
-    cw = code_words(d)
+    cw = code_words(d, enc)
     if cw == 0:
-        raise QuiverError(-3, "qv_encode")
+        raise QuiverError(-3 if enc in (ENC_SM, ENC_SIGN1, ENC_SQ2) else -1, "qv_encode")
     codes = torch.empty((n, cw), dtype=torch.int64, device=x.device)
     status = torch.empty((n,), dtype=torch.int32, device=x.device) if want_status else None
-    _check(_lib.qv_encode(x.data_ptr(), n, d, codes.data_ptr(), status.data_ptr() if want_status else None,
-                          _stream()), "qv_encode")
+    _check(_lib.qv_encode_enc(x.data_ptr(), n, d, int(enc), codes.data_ptr(),
+                              status.data_ptr() if want_status else None, _stream()), "qv_encode_enc")
     return (codes, status) if want_status else codes
 
 
-def bq_distance(codes_a: torch.Tensor, ia: torch.Tensor, codes_b: torch.Tensor, ib: torch.Tensor, d: int):
-    """qv_bq_distance: symmetric code distance for index pairs -> int32 [npairs] (uint32 values)."""
+def bq_distance(codes_a: torch.Tensor, ia: torch.Tensor, codes_b: torch.Tensor, ib: torch.Tensor, d: int,
+                enc: int = ENC_SM):
+    """qv_bq_distance(_enc): code distance for index pairs -> int32 [npairs] (uint32 values)."""
     codes_a = _dev(codes_a, torch.int64, "codes_a")
     codes_b = _dev(codes_b, torch.int64, "codes_b")
     ia = _dev(ia, torch.int64, "ia")
     ib = _dev(ib, torch.int64, "ib")
-    cw = code_words(d)
+    cw = code_words(d, enc)
     if codes_a.shape[1] != cw or codes_b.shape[1] != cw or ia.shape != ib.shape:
         raise ValueError("shape mismatch")
     if ia.numel() and (int(ia.min()) < 0 or int(ia.max()) >= codes_a.shape[0] or int(ib.min()) < 0 or
                        int(ib.max()) >= codes_b.shape[0]):
         raise IndexError("pair index out of range")
     out = torch.empty(ia.shape, dtype=torch.int32, device=codes_a.device)
-    _check(_lib.qv_bq_distance(codes_a.data_ptr(), ia.data_ptr(), codes_b.data_ptr(), ib.data_ptr(), ia.numel(),
-                               int(d), out.data_ptr(), _stream()), "qv_bq_distance")
+    _check(_lib.qv_bq_distance_enc(codes_a.data_ptr(), ia.data_ptr(), codes_b.data_ptr(), ib.data_ptr(), ia.numel(),
+                                   int(d), int(enc), out.data_ptr(), _stream()), "qv_bq_distance_enc")
     return out
 
 
@@ -176,11 +192,11 @@ def gather_probe(codes: torch.Tensor, d: int, ids: torch.Tensor) -> None:
                                 sink.data_ptr(), _stream()), "qv_gather_probe")
 
 
-def bq_scan(codes: torch.Tensor, qcodes: torch.Tensor, d: int, K: int):
-    """qv_bq_scan: brute force in code space -> (ids, dist) int32 [nq, K] holding uint32 values."""
+def bq_scan(codes: torch.Tensor, qcodes: torch.Tensor, d: int, K: int, enc: int = ENC_SM):
+    """qv_bq_scan(_enc): brute force in code space -> (ids, dist) int32 [nq, K] holding uint32 values."""
     codes = _dev(codes, torch.int64, "codes")
     qcodes = _dev(qcodes, torch.int64, "qcodes")
-    cw = code_words(d)
+    cw = code_words(d, enc)
     if codes.shape[1] != cw or qcodes.shape[1] != cw:
         raise ValueError("code width does not match d")
     n, nq = codes.shape[0], qcodes.shape[0]
@@ -188,8 +204,8 @@ def bq_scan(codes: torch.Tensor, qcodes: torch.Tensor, d: int, K: int):
     dist = torch.empty((nq, K), dtype=torch.int32, device=codes.device)
     need = int(_lib.qv_bq_scan_workspace_bytes(n, nq, K))
     ws = torch.empty((max(need, 256),), dtype=torch.uint8, device=codes.device)
-    _check(_lib.qv_bq_scan(codes.data_ptr(), n, int(d), qcodes.data_ptr(), nq, int(K), ids.data_ptr(),
-                           dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "qv_bq_scan")
+    _check(_lib.qv_bq_scan_enc(codes.data_ptr(), n, int(d), int(enc), qcodes.data_ptr(), nq, int(K), ids.data_ptr(),
+                               dist.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "qv_bq_scan_enc")
     return ids, dist
 
 
@@ -206,17 +222,18 @@ def topk_overlap(a: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
 
 
 def build_graph(codes: torch.Tensor, d: int, R: int, L: int, alpha: float, entry: int,
-                max_batch: int = 1 << 20) -> torch.Tensor:
-    """qv_build_graph: batch-synchronous construction in code space -> adj int32 [n, R] (uint32 bits)."""
+                max_batch: int = 1 << 20, enc: int = ENC_SM) -> torch.Tensor:
+    """qv_build_graph(_enc): batch-synchronous construction in code space -> adj int32 [n, R] (uint32 bits)."""
     codes = _dev(codes, torch.int64, "codes")
     n = codes.shape[0]
-    if codes.shape[1] != code_words(d):
+    if codes.shape[1] != code_words(d, enc):
         raise ValueError("code width does not match d")
     need = int(_lib.qv_build_workspace_bytes(n, int(d), int(R), int(L), int(max_batch)))
     ws = torch.empty((max(need, 256),), dtype=torch.uint8, device=codes.device)
     adj = torch.empty((n, R), dtype=torch.int32, device=codes.device)
-    _check(_lib.qv_build_graph(codes.data_ptr(), n, int(d), int(R), int(L), float(alpha), int(entry), int(max_batch),
-                               adj.data_ptr(), ws.data_ptr(), ws.numel(), _stream()), "qv_build_graph")
+    _check(_lib.qv_build_graph_enc(codes.data_ptr(), n, int(d), int(enc), int(R), int(L), float(alpha), int(entry),
+                                   int(max_batch), adj.data_ptr(), ws.data_ptr(), ws.numel(), _stream()),
+           "qv_build_graph_enc")
     return adj
 
 
@@ -250,7 +267,7 @@ class Index:
     cold data of the method and are only touched by the rerank.
     """
 
-    def __init__(self, adj: torch.Tensor, codes: torch.Tensor, vecs: torch.Tensor, entry: int):
+    def __init__(self, adj: torch.Tensor, codes: torch.Tensor, vecs: torch.Tensor, entry: int, enc: int = ENC_SM):
         adj = _dev(adj, torch.int32, "adj")
         codes = _dev(codes, torch.int64, "codes")
         if isinstance(vecs, torch.Tensor) and not vecs.is_cuda and vecs.is_pinned():
@@ -260,7 +277,7 @@ class Index:
         else:
             vecs = _dev(vecs, torch.float32, "vecs")
         n, d = vecs.shape
-        if adj.shape[0] != n or codes.shape != (n, code_words(d)):
+        if adj.shape[0] != n or codes.shape != (n, code_words(d, enc)):
             raise ValueError("adj/codes/vecs shapes do not agree")
         self.n, self.d, self.R = n, d, adj.shape[1]
         self._keep = (adj, codes, vecs)  # the library borrows these buffers
@@ -269,6 +286,8 @@ class Index:
                                   int(entry)), "qv_index_load")
         self._h = h
         self._timer = None
+        if enc != ENC_SM:
+            _check(_lib.qv_index_set_encoding(h, int(enc)), "qv_index_set_encoding")
 
     def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0,
                    visited_mode: int = 0) -> None:

@@ -10,8 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquiver_hip.so")
 SOURCES = ["api.hip", "encode.hip", "rerank.hip", "scan.hip", "build.hip"]
-# the search kernel is compiled once per code width (64-bit words per bit-plane; 0 = any width at run time)
-SEARCH_WIDTHS = [12, 16, 24, 48, 8, 6, 2, 0]
+# the search kernel is compiled once per (encoding, code width) pair (64-bit words per bit-plane; 0 = any width
+# at run time); the ablation encodings 1 and 2 exist for 768-d and for the run-time width only
+SEARCH_VARIANTS = [(0, 12), (0, 16), (0, 24), (0, 48), (0, 8), (0, 6), (0, 2), (0, 0), (1, 12), (2, 12), (1, 0), (2, 0)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -30,7 +31,8 @@ def is_current() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and is_current():
         return LIB
-    jobs = [("search.hip", os.path.join(CSRC, f"search_w{w}.o"), [f"-DQV_SEARCH_WIDTH={w}"]) for w in SEARCH_WIDTHS]
+    jobs = [("search.hip", os.path.join(CSRC, f"search_e{e}_w{w}.o"), [f"-DQV_SEARCH_ENC={e}", f"-DQV_SEARCH_WIDTH={w}"])
+            for e, w in SEARCH_VARIANTS]
     jobs += [(s, os.path.join(CSRC, s.replace(".hip", ".o")), []) for s in SOURCES]
     objs = [j[1] for j in jobs]
 

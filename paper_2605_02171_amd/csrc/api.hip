@@ -59,29 +59,45 @@ struct qv_index {
     int lanes_per_row;  // <= 0: choose from d
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
     int visited_mode;   // 0: choose from ef; QV_VISITED_EXACT; QV_VISITED_CACHE
+    int encoding;       // QV_ENC_*: what `codes` holds and what the queries are encoded to
     qv_timer* timer;
 };
 
 extern "C" {
 
-int qv_code_words(int d) { return (d < 1 || d > QV_MAX_DIM) ? 0 : 2 * ((d + 63) / 64); }
+static bool enc_ok(int encoding) { return encoding == QV_ENC_SM || encoding == QV_ENC_SIGN1 || encoding == QV_ENC_SQ2; }
+
+int qv_code_words(int d) { return qv_code_words_enc(d, QV_ENC_SM); }
+
+int qv_code_words_enc(int d, int encoding) {
+    return (d < 1 || d > QV_MAX_DIM || !enc_ok(encoding)) ? 0 : qv::code_row_words((d + 63) / 64, encoding);
+}
 
 int qv_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, void* stream) {
+    return qv_encode_enc(x, n, d, QV_ENC_SM, codes, status, stream);
+}
+
+int qv_encode_enc(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status, void* stream) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (n < 0) return QV_ERR_INVALID_ARG;
+    if (n < 0 || !enc_ok(encoding)) return QV_ERR_INVALID_ARG;
     if (n == 0) return QV_OK;
     if (!x || !codes) return QV_ERR_NULL;
-    hipError_t e = qv::launch_encode(x, n, d, codes, status, (hipStream_t)stream);
+    hipError_t e = qv::launch_encode(x, n, d, encoding, codes, status, (hipStream_t)stream);
     return e == hipSuccess ? QV_OK : hip_fail(e, "encode launch");
 }
 
 int qv_bq_distance(const uint64_t* codes_a, const int64_t* ia, const uint64_t* codes_b, const int64_t* ib,
                    int64_t npairs, int d, uint32_t* out, void* stream) {
+    return qv_bq_distance_enc(codes_a, ia, codes_b, ib, npairs, d, QV_ENC_SM, out, stream);
+}
+
+int qv_bq_distance_enc(const uint64_t* codes_a, const int64_t* ia, const uint64_t* codes_b, const int64_t* ib,
+                       int64_t npairs, int d, int encoding, uint32_t* out, void* stream) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (npairs < 0) return QV_ERR_INVALID_ARG;
+    if (npairs < 0 || !enc_ok(encoding)) return QV_ERR_INVALID_ARG;
     if (npairs == 0) return QV_OK;
     if (!codes_a || !codes_b || !ia || !ib || !out) return QV_ERR_NULL;
-    hipError_t e = qv::launch_bq_distance(codes_a, ia, codes_b, ib, npairs, d, out, (hipStream_t)stream);
+    hipError_t e = qv::launch_bq_distance(codes_a, ia, codes_b, ib, npairs, d, encoding, out, (hipStream_t)stream);
     return e == hipSuccess ? QV_OK : hip_fail(e, "bq_distance launch");
 }
 
@@ -103,14 +119,19 @@ size_t qv_bq_scan_workspace_bytes(int64_t n, int64_t nq, int K) {
 
 int qv_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K, uint32_t* ids,
                uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream) {
+    return qv_bq_scan_enc(codes, n, d, QV_ENC_SM, qcodes, nq, K, ids, dist, workspace, workspace_bytes, stream);
+}
+
+int qv_bq_scan_enc(const uint64_t* codes, int64_t n, int d, int encoding, const uint64_t* qcodes, int64_t nq, int K,
+                   uint32_t* ids, uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (n < 0 || n >= 0xFFFFFFFFll || nq < 0 || nq > 64ll * 0x7FFFFFFF || K < 1 || K > QV_MAX_SCAN_K)
+    if (n < 0 || n >= 0xFFFFFFFFll || nq < 0 || nq > 64ll * 0x7FFFFFFF || K < 1 || K > QV_MAX_SCAN_K || !enc_ok(encoding))
         return QV_ERR_INVALID_ARG;
     if (nq == 0) return QV_OK;
     if ((n > 0 && !codes) || !qcodes || !ids || !dist) return QV_ERR_NULL;
     if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < qv_bq_scan_workspace_bytes(n, nq, K))
         return QV_ERR_WORKSPACE;
-    hipError_t e = qv::launch_bq_scan(codes, n, d, qcodes, nq, K, static_cast<uint64_t*>(workspace), ids, dist,
+    hipError_t e = qv::launch_bq_scan(codes, n, d, encoding, qcodes, nq, K, static_cast<uint64_t*>(workspace), ids, dist,
                                       (hipStream_t)stream);
     return e == hipSuccess ? QV_OK : hip_fail(e, "code scan launch");
 }
@@ -128,19 +149,25 @@ static bool build_args_ok(int64_t n, int d, int R, int L) {
 }
 
 size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch) {
-    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !qv::build_supports_width((d + 63) / 64)) return 0;
+    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !qv::build_supports_width((d + 63) / 64, QV_ENC_SM)) return 0;
     return qv::build_workspace_bytes(n, R, L, max_batch);
 }
 
 int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
                    int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream) {
+    return qv_build_graph_enc(codes, n, d, QV_ENC_SM, R, L, alpha, entry, max_batch, adj, workspace, workspace_bytes, stream);
+}
+
+int qv_build_graph_enc(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
+                       int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !(alpha >= 1.0) || (int64_t)entry >= n) return QV_ERR_INVALID_ARG;
-    if (!qv::build_supports_width((d + 63) / 64)) return QV_ERR_UNSUPPORTED;
+    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !(alpha >= 1.0) || (int64_t)entry >= n || !enc_ok(encoding))
+        return QV_ERR_INVALID_ARG;
+    if (!qv::build_supports_width((d + 63) / 64, encoding)) return QV_ERR_UNSUPPORTED;
     if (!codes || !adj) return QV_ERR_NULL;
     if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < qv::build_workspace_bytes(n, R, L, max_batch))
         return QV_ERR_WORKSPACE;
-    hipError_t e = qv::build_graph(codes, n, d, R, L, alpha, entry, max_batch, adj, workspace, (hipStream_t)stream);
+    hipError_t e = qv::build_graph(codes, n, d, encoding, R, L, alpha, entry, max_batch, adj, workspace, (hipStream_t)stream);
     return e == hipSuccess ? QV_OK : hip_fail(e, "graph construction");
 }
 
@@ -154,7 +181,7 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->encoding = QV_ENC_SM; ix->timer = nullptr;
     *out = ix;
     return QV_OK;
 }
@@ -171,6 +198,13 @@ int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, i
     index->lanes_per_row = lanes_per_row;
     index->table_format = table_format;
     index->visited_mode = visited_mode;
+    return QV_OK;
+}
+
+int qv_index_set_encoding(qv_index* index, int encoding) {
+    if (!index) return QV_ERR_NULL;
+    if (!enc_ok(encoding)) return QV_ERR_INVALID_ARG;
+    index->encoding = encoding;
     return QV_OK;
 }
 
@@ -201,12 +235,12 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     if (ev && (e = hipEventRecord(ev[0], stream)) != hipSuccess) return hip_fail(e, "event record");
 
     // Stage 1 preamble: the query's own code
-    e = qv::launch_encode(queries, nq, index->d, qcodes, nullptr, stream);
+    e = qv::launch_encode(queries, nq, index->d, index->encoding, qcodes, nullptr, stream);
     if (e != hipSuccess) return hip_fail(e, "query encode launch");
     if (ev && (e = hipEventRecord(ev[1], stream)) != hipSuccess) return hip_fail(e, "event record");
 
     qv::SearchParams sp;
-    sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes;
+    sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes; sp.encoding = index->encoding;
     sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
     // Visited set.  Default: a cache of 4096 slots (8 KB of 16-bit tags): with the list and the merge area a
     // query then needs about 10 KB of LDS, so 16 queries fit a compute unit and registers, not LDS, bound the

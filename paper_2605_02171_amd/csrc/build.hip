@@ -48,51 +48,67 @@ __device__ void sort_keys(uint64_t* buf, int m, int lane) {
 
 __device__ __forceinline__ int pow2_at_least(int c) { return c <= 64 ? 64 : (c <= 128 ? 128 : 256); }
 
+// one 32-bit step of the distance between two codes (a0, a1 / b0, b1: first and second plane dword of each) under
+// the three encodings: Sign-Magnitude (Table 1 as three popcounts), 1-bit sign (Hamming), 2-bit uniform quantiser
+// (L1 on levels = Hamming distance of the three thermometer planes hi|lo, hi, hi&lo)
+template <int ENC>
+__device__ __forceinline__ void pair_accumulate(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, uint32_t& c1,
+                                                uint32_t& c2, uint32_t& c3) {
+    if constexpr (ENC == ENC_SM) {
+        const uint32_t x = a0 ^ b0;
+        c1 += __popc(x);
+        c2 += __popc(__builtin_amdgcn_bitop3_b32(x, a1, b1, 0xE0));
+        c3 += __popc(__builtin_amdgcn_bitop3_b32(x, a1, b1, 0x80));
+    } else if constexpr (ENC == ENC_SIGN1) {
+        c1 += __popc(a0 ^ b0);
+    } else {
+        c1 += __popc(__builtin_amdgcn_bitop3_b32(a1, a0, b0 | b1, 0x56));
+        c2 += __popc(a1 ^ b1);
+        c3 += __popc(__builtin_amdgcn_bitop3_b32(a1, a0, b0 & b1, 0x6A));
+    }
+}
+template <int ENC>
+__device__ __forceinline__ uint32_t pair_distance(uint32_t c1, uint32_t c2, uint32_t c3) {
+    return ENC == ENC_SM ? c1 + c2 + 2u * c3 : c1 + c2 + c3;
+}
+
 // distance between a wave-uniform code (scalar pointer) and a per-lane code in memory
-template <int NW_T>
+template <int ENC, int NW_T>
 __device__ __forceinline__ uint32_t dist_uniform_vs_row(const uint32_t* __restrict__ cu, const uint64_t* __restrict__ codes,
                                                         uint32_t v) {
-    constexpr int DW = 2 * NW_T;
-    const uint32_t* r = reinterpret_cast<const uint32_t*>(codes + (int64_t)v * (2 * NW_T));
+    constexpr int DW = 2 * NW_T, PLANES = ENC == ENC_SIGN1 ? 1 : 2;
+    const uint32_t* r = reinterpret_cast<const uint32_t*>(codes + (int64_t)v * (PLANES * NW_T));
     uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-    for (int w = 0; w < DW; ++w) {
-        const uint32_t x = cu[w] ^ r[w], sv = r[DW + w], su = cu[DW + w];
-        c1 += __popc(x);
-        c2 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, su, 0xE0));
-        c3 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, su, 0x80));
-    }
-    return c1 + c2 + 2u * c3;
+    for (int w = 0; w < DW; ++w)
+        pair_accumulate<ENC>(r[w], PLANES == 2 ? r[DW + w] : 0u, cu[w], PLANES == 2 ? cu[DW + w] : 0u, c1, c2, c3);
+    return pair_distance<ENC>(c1, c2, c3);
 }
 
 // Algorithm 1 over buf[0..count) (sorted ascending, ids distinct, self excluded).  sel[0..ns) receives the ids.
-template <int NW_T>
+template <int ENC, int NW_T>
 __device__ int select_edges_dev(const uint64_t* __restrict__ codes, const uint64_t* buf, int count, int R, double alpha,
                                 uint32_t* sel, int lane) {
-    constexpr int DW = 2 * NW_T;
-    uint32_t sc[2 * DW];  // the code of the neighbour this lane stands for
+    constexpr int DW = 2 * NW_T, PLANES = ENC == ENC_SIGN1 ? 1 : 2;
+    uint32_t sc[PLANES * DW];  // the code of the neighbour this lane stands for
 #pragma unroll
-    for (int w = 0; w < 2 * DW; ++w) sc[w] = 0;
+    for (int w = 0; w < PLANES * DW; ++w) sc[w] = 0;
     int ns = 0;
     for (int i = 0; i < count; ++i) {
         const uint64_t key = buf[i];
         const uint32_t c = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)key);
         const uint32_t dct = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(key >> 32));
-        const uint32_t* crow = reinterpret_cast<const uint32_t*>(codes + (int64_t)c * (2 * NW_T));  // wave-uniform
+        const uint32_t* crow = reinterpret_cast<const uint32_t*>(codes + (int64_t)c * (PLANES * NW_T));  // wave-uniform
         uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-        for (int w = 0; w < DW; ++w) {
-            const uint32_t x = crow[w] ^ sc[w], sv = crow[DW + w], ss = sc[DW + w];
-            c1 += __popc(x);
-            c2 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, ss, 0xE0));
-            c3 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, ss, 0x80));
-        }
-        const uint32_t dcs = c1 + c2 + 2u * c3;
+        for (int w = 0; w < DW; ++w)
+            pair_accumulate<ENC>(sc[w], PLANES == 2 ? sc[DW + w] : 0u, crow[w], PLANES == 2 ? crow[DW + w] : 0u, c1, c2, c3);
+        const uint32_t dcs = pair_distance<ENC>(c1, c2, c3);
         const bool viol = lane < ns && !((double)dct <= alpha * (double)dcs);
         if (!__any(viol)) {
             if (lane == ns) {
 #pragma unroll
-                for (int w = 0; w < 2 * DW; ++w) sc[w] = crow[w];
+                for (int w = 0; w < PLANES * DW; ++w) sc[w] = crow[w];
             }
             if (lane == 0) sel[ns] = c;
             ns++;
@@ -116,7 +132,7 @@ struct BuildParams {
     uint64_t* pairs;            // [bs*R] (target << 32 | source), B_NONE where unused
 };
 
-template <int NW_T>
+template <int ENC, int NW_T>
 __global__ __launch_bounds__(64) void forward_select_kernel(BuildParams p) {
     __shared__ uint64_t buf[BUF];
     __shared__ uint32_t sel[64];
@@ -143,8 +159,8 @@ __global__ __launch_bounds__(64) void forward_select_kernel(BuildParams p) {
         bool dup = false;
         for (int e = 0; e < nc; ++e) dup |= (uint32_t)buf[e] == v;
         const bool add = has && !dup;
-        const uint32_t* ct = reinterpret_cast<const uint32_t*>(p.codes + (int64_t)t * (2 * NW_T));
-        const uint32_t dv = add ? dist_uniform_vs_row<NW_T>(ct, p.codes, v) : 0u;
+        const uint32_t* ct = reinterpret_cast<const uint32_t*>(p.codes + (int64_t)t * ((ENC == ENC_SIGN1 ? 1 : 2) * NW_T));
+        const uint32_t dv = add ? dist_uniform_vs_row<ENC, NW_T>(ct, p.codes, v) : 0u;
         const uint64_t am = __ballot(add);
         const int pos = total + __popcll(am & ((1ull << lane) - 1ull));
         if (add && pos < BUF) buf[pos] = ((uint64_t)dv << 32) | v;
@@ -152,7 +168,7 @@ __global__ __launch_bounds__(64) void forward_select_kernel(BuildParams p) {
         bsync();
     }
     sort_keys(buf, pow2_at_least(total), lane);
-    const int ns = select_edges_dev<NW_T>(p.codes, buf, total - removed, p.R, p.alpha, sel, lane);
+    const int ns = select_edges_dev<ENC, NW_T>(p.codes, buf, total - removed, p.R, p.alpha, sel, lane);
     if (lane < p.R) {
         const uint32_t s = lane < ns ? sel[lane] : EMPTY_ID;
         p.adj[(int64_t)t * p.R + lane] = s;
@@ -160,7 +176,7 @@ __global__ __launch_bounds__(64) void forward_select_kernel(BuildParams p) {
     }
 }
 
-template <int NW_T>
+template <int ENC, int NW_T>
 __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64_t* __restrict__ sorted,
                                                      int64_t n_pairs) {
     __shared__ uint64_t buf[BUF];
@@ -177,7 +193,7 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
     rowcopy[lane] = v;
     const uint64_t occupied = __ballot(v != EMPTY_ID);
     const int deg = __popcll(occupied);
-    const uint32_t* cb = reinterpret_cast<const uint32_t*>(p.codes + (int64_t)b * (2 * NW_T));  // wave-uniform
+    const uint32_t* cb = reinterpret_cast<const uint32_t*>(p.codes + (int64_t)b * ((ENC == ENC_SIGN1 ? 1 : 2) * NW_T));  // wave-uniform
     bsync();
 
     int cnt = 0;  // new candidates in buf[0..cnt)
@@ -187,7 +203,7 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
         const uint32_t t = (uint32_t)k;
         bool ok = in_run && t != b;
         for (int j = 0; j < p.R; ++j) ok &= rowcopy[j] != t;
-        const uint32_t dt = ok ? dist_uniform_vs_row<NW_T>(cb, p.codes, t) : 0u;
+        const uint32_t dt = ok ? dist_uniform_vs_row<ENC, NW_T>(cb, p.codes, t) : 0u;
         const uint64_t om = __ballot(ok);
         const int m = __popcll(om);
         if (cnt + m > BUF) {  // make room: keep the nearest MAX_NEW seen so far
@@ -216,14 +232,14 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
     }
     // re-select from (old row U new candidates)
     const bool old = lane < p.R && v != EMPTY_ID;
-    const uint32_t dv = old ? dist_uniform_vs_row<NW_T>(cb, p.codes, v) : 0u;
+    const uint32_t dv = old ? dist_uniform_vs_row<ENC, NW_T>(cb, p.codes, v) : 0u;
     if (old) buf[cnt + __popcll(occupied & ((1ull << lane) - 1ull))] = ((uint64_t)dv << 32) | v;
     const int total = cnt + deg;  // <= MAX_NEW + 64 = BUF
     const int m2 = pow2_at_least(total);
     for (int e = total + lane; e < m2; e += 64) buf[e] = B_NONE;
     bsync();
     sort_keys(buf, m2, lane);
-    const int ns = select_edges_dev<NW_T>(p.codes, buf, total, p.R, p.alpha, sel, lane);
+    const int ns = select_edges_dev<ENC, NW_T>(p.codes, buf, total, p.R, p.alpha, sel, lane);
     if (lane < p.R) p.adj[(int64_t)b * p.R + lane] = lane < ns ? sel[lane] : EMPTY_ID;
 }
 
@@ -234,29 +250,42 @@ size_t build_sort_temp_bytes(int64_t max_pairs) {
     return bytes;
 }
 
-bool build_supports_width(int nw) { return nw == 2 || nw == 6 || nw == 8 || nw == 12 || nw == 16; }
+bool build_supports_width(int nw, int encoding) {
+    if (encoding != ENC_SM) return nw == 2 || nw == 12;
+    return nw == 2 || nw == 6 || nw == 8 || nw == 12 || nw == 16;
+}
 
-template <int NW_T>
+template <int ENC, int NW_T>
 static hipError_t launch_batch(const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
                                hipStream_t stream) {
-    hipLaunchKernelGGL(forward_select_kernel<NW_T>, dim3((unsigned)bp.bs), dim3(64), 0, stream, bp);
+    hipLaunchKernelGGL((forward_select_kernel<ENC, NW_T>), dim3((unsigned)bp.bs), dim3(64), 0, stream, bp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t n_pairs = bp.bs * bp.R;
     e = hipcub::DeviceRadixSort::SortKeys(temp, temp_bytes, bp.pairs, sorted, (int)n_pairs, 0, 64, stream);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(reverse_kernel<NW_T>, dim3((unsigned)n_pairs), dim3(64), 0, stream, bp, sorted, n_pairs);
+    hipLaunchKernelGGL((reverse_kernel<ENC, NW_T>), dim3((unsigned)n_pairs), dim3(64), 0, stream, bp, sorted, n_pairs);
     return hipGetLastError();
 }
 
-hipError_t launch_build_batch(int nw, const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
+hipError_t launch_build_batch(int nw, int encoding, const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
                               hipStream_t stream) {
+    if (encoding == ENC_SIGN1) {
+        if (nw == 2) return launch_batch<ENC_SIGN1, 2>(bp, sorted, temp, temp_bytes, stream);
+        if (nw == 12) return launch_batch<ENC_SIGN1, 12>(bp, sorted, temp, temp_bytes, stream);
+        return hipErrorInvalidValue;
+    }
+    if (encoding == ENC_SQ2) {
+        if (nw == 2) return launch_batch<ENC_SQ2, 2>(bp, sorted, temp, temp_bytes, stream);
+        if (nw == 12) return launch_batch<ENC_SQ2, 12>(bp, sorted, temp, temp_bytes, stream);
+        return hipErrorInvalidValue;
+    }
     switch (nw) {
-        case 2: return launch_batch<2>(bp, sorted, temp, temp_bytes, stream);
-        case 6: return launch_batch<6>(bp, sorted, temp, temp_bytes, stream);
-        case 8: return launch_batch<8>(bp, sorted, temp, temp_bytes, stream);
-        case 12: return launch_batch<12>(bp, sorted, temp, temp_bytes, stream);
-        case 16: return launch_batch<16>(bp, sorted, temp, temp_bytes, stream);
+        case 2: return launch_batch<ENC_SM, 2>(bp, sorted, temp, temp_bytes, stream);
+        case 6: return launch_batch<ENC_SM, 6>(bp, sorted, temp, temp_bytes, stream);
+        case 8: return launch_batch<ENC_SM, 8>(bp, sorted, temp, temp_bytes, stream);
+        case 12: return launch_batch<ENC_SM, 12>(bp, sorted, temp, temp_bytes, stream);
+        case 16: return launch_batch<ENC_SM, 16>(bp, sorted, temp, temp_bytes, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -278,7 +307,7 @@ size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch) {
            up256(build_sort_temp_bytes(mb * R)) + 256;
 }
 
-hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream) {
     const int nw = (d + 63) / 64;
     const int64_t mb = build_max_batch(n, max_batch);
@@ -294,7 +323,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, do
     hipError_t e = hipMemsetAsync(adj, 0xFF, (size_t)n * R * 4, stream);
     if (e != hipSuccess) return e;
     SearchParams sp{};
-    sp.adj = adj; sp.codes = codes; sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
+    sp.adj = adj; sp.codes = codes; sp.encoding = encoding; sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
     sp.cand_ids = cand_ids; sp.cand_dist = cand_dist; sp.n_cand = n_cand;
     sp.n_expanded = nullptr; sp.n_evals = nullptr; sp.status = nullptr; sp.visit_order = nullptr; sp.visit_cap = 0;
     plan_visited_table(sp, 4096, true, true);  // visited set as a cache: same lists, more queries per compute unit
@@ -306,12 +335,12 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, do
         if (bs < 1) bs = 1;
         if (bs > mb) bs = mb;
         if (done + bs > n) bs = n - done;
-        sp.qcodes = codes + done * (int64_t)(2 * nw);
+        sp.qcodes = codes + done * (int64_t)code_row_words(nw, encoding);
         sp.nq = bs;
         e = launch_beam_search(sp, 0, stream);
         if (e != hipSuccess) return e;
         bp.done = done; bp.bs = bs;
-        e = launch_build_batch(nw, bp, sorted, temp, temp_bytes, stream);
+        e = launch_build_batch(nw, encoding, bp, sorted, temp, temp_bytes, stream);
         if (e != hipSuccess) return e;
         done += bs;
     }

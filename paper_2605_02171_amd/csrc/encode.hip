@@ -198,21 +198,95 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel(const float* __r
     exact_magnitude_plane(xv, d, W, cv, acc[wv], digits[wv], lane);
 }
 
-// out[p] = symmetric distance of code rows ia[p] (in a) and ib[p] (in b): one thread per pair
+// ---- the two encodings of the paper's ablation (Sec. 5.4 "Encoding Ablation", Table 10) ----------------
+// 1-bit sign: the sign plane alone.  One wave per vector, 64 dimensions per ballot.
+__global__ __launch_bounds__(64 * ENC_WAVES) void encode_sign1_kernel(const float* __restrict__ x, int64_t n, int d,
+                                                                      uint64_t* __restrict__ codes,
+                                                                      uint32_t* __restrict__ status) {
+    const int lane = threadIdx.x & 63;
+    const int64_t v = (int64_t)blockIdx.x * ENC_WAVES + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int W = (d + 63) >> 6;
+    const float* xv = x + v * (int64_t)d;
+    bool finite = true;
+    for (int w = 0; w < W; ++w) {
+        const int i = (w << 6) + lane;
+        const float xi = i < d ? xv[i] : 0.0f;
+        finite &= (__float_as_uint(xi) & 0x7F800000u) != 0x7F800000u;
+        const uint64_t pw = __ballot(is_positive(xi));
+        if (lane == 0) codes[v * (int64_t)W + w] = pw;
+    }
+    const bool all_finite = __all(finite);
+    if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
+}
+
+// 2-bit uniform quantiser: four equal-width buckets over the vector's own range [min, max] (the paper names no
+// range; this is the reading taken).  level = number of k in {1, 2, 3} with 4 (x - min) >= k (max - min), every
+// difference and product in IEEE double in exactly this form, so that any implementation gets the same bits; a
+// constant vector has level 3 everywhere.  Planes: low bit of the level, then high bit.
+__global__ __launch_bounds__(64 * ENC_WAVES) void encode_sq2_kernel(const float* __restrict__ x, int64_t n, int d,
+                                                                    uint64_t* __restrict__ codes,
+                                                                    uint32_t* __restrict__ status) {
+    const int lane = threadIdx.x & 63;
+    const int64_t v = (int64_t)blockIdx.x * ENC_WAVES + (threadIdx.x >> 6);
+    if (v >= n) return;
+    const int W = (d + 63) >> 6;
+    const float* xv = x + v * (int64_t)d;
+    float mn = xv[0], mx = xv[0];
+    bool finite = true;
+    for (int i = lane; i < d; i += 64) {
+        const float xi = xv[i];
+        finite &= (__float_as_uint(xi) & 0x7F800000u) != 0x7F800000u;
+        mn = xi < mn ? xi : mn;
+        mx = xi > mx ? xi : mx;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float a = __shfl_xor(mn, off), b = __shfl_xor(mx, off);
+        mn = a < mn ? a : mn;
+        mx = b > mx ? b : mx;
+    }
+    const bool all_finite = __all(finite);
+    const double lo = (double)mn, width = (double)mx - (double)mn;
+    const double w2 = 2.0 * width, w3 = 3.0 * width;
+    for (int w = 0; w < W; ++w) {
+        const int i = (w << 6) + lane;
+        int level = 0;
+        if (i < d) {
+            const double t = ((double)xv[i] - lo) * 4.0;
+            level = (t >= width ? 1 : 0) + (t >= w2 ? 1 : 0) + (t >= w3 ? 1 : 0);
+        }
+        const uint64_t lw = __ballot(level & 1), hw = __ballot(level & 2);
+        if (lane == 0) codes[v * (int64_t)(2 * W) + w] = lw;
+        if (lane == 1) codes[v * (int64_t)(2 * W) + W + w] = hw;
+    }
+    if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
+}
+
+// out[p] = distance of code rows ia[p] (in a) and ib[p] (in b) under the given encoding: one thread per pair
 __global__ void bq_distance_kernel(const uint64_t* __restrict__ a, const int64_t* __restrict__ ia,
                                    const uint64_t* __restrict__ b, const int64_t* __restrict__ ib, int64_t npairs,
-                                   int W, uint32_t* __restrict__ out) {
+                                   int W, int encoding, uint32_t* __restrict__ out) {
     int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= npairs) return;
-    const uint64_t* ca = a + ia[p] * (int64_t)(2 * W);
-    const uint64_t* cb = b + ib[p] * (int64_t)(2 * W);
+    const int rw = code_row_words_dev(W, encoding);
+    const uint64_t* ca = a + ia[p] * (int64_t)rw;
+    const uint64_t* cb = b + ib[p] * (int64_t)rw;
     uint32_t c1 = 0, c2 = 0, c3 = 0;
     for (int w = 0; w < W; ++w) {
-        uint64_t X = ca[w] ^ cb[w];
-        uint64_t sa = ca[W + w], sb = cb[W + w];
-        c1 += __popcll(X);
-        c2 += __popcll(X & (sa | sb));
-        c3 += __popcll(X & sa & sb);
+        if (encoding == ENC_SIGN1) {
+            c1 += __popcll(ca[w] ^ cb[w]);
+        } else if (encoding == ENC_SQ2) {
+            const uint64_t la = ca[w], ha = ca[W + w], lb = cb[w], hb = cb[W + w];
+            c1 += __popcll((la | ha) ^ (lb | hb)) + __popcll((la & ha) ^ (lb & hb));
+            c2 += __popcll(ha ^ hb);
+        } else {
+            uint64_t X = ca[w] ^ cb[w];
+            uint64_t sa = ca[W + w], sb = cb[W + w];
+            c1 += __popcll(X);
+            c2 += __popcll(X & (sa | sb));
+            c3 += __popcll(X & sa & sb);
+        }
     }
     out[p] = c1 + c2 + 2u * c3;
 }
@@ -255,9 +329,18 @@ hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids
     return hipGetLastError();
 }
 
-hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, hipStream_t stream) {
+hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status,
+                         hipStream_t stream) {
     if (n == 0) return hipSuccess;
     dim3 grid((unsigned)((n + ENC_WAVES - 1) / ENC_WAVES)), block(64 * ENC_WAVES);
+    if (encoding == ENC_SIGN1) {
+        hipLaunchKernelGGL(encode_sign1_kernel, grid, block, 0, stream, x, n, d, codes, status);
+        return hipGetLastError();
+    }
+    if (encoding == ENC_SQ2) {
+        hipLaunchKernelGGL(encode_sq2_kernel, grid, block, 0, stream, x, n, d, codes, status);
+        return hipGetLastError();
+    }
     const unsigned full = 256 * 8 * 16;  // 16 rounds of 8 workgroups per CU
     dim3 pgrid(grid.x < full ? grid.x : full);
     switch ((d + 63) / 64) {
@@ -271,11 +354,11 @@ hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint
 }
 
 hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
-                              int64_t npairs, int d, uint32_t* out, hipStream_t stream) {
+                              int64_t npairs, int d, int encoding, uint32_t* out, hipStream_t stream) {
     if (npairs == 0) return hipSuccess;
     int W = (d + 63) / 64;
     dim3 grid((unsigned)((npairs + 255) / 256));
-    hipLaunchKernelGGL(bq_distance_kernel, grid, dim3(256), 0, stream, a, ia, b, ib, npairs, W, out);
+    hipLaunchKernelGGL(bq_distance_kernel, grid, dim3(256), 0, stream, a, ia, b, ib, npairs, W, encoding, out);
     return hipGetLastError();
 }
 

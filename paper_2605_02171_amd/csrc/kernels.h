@@ -6,14 +6,19 @@
 namespace qv {
 
 constexpr uint32_t EMPTY_ID = 0xFFFFFFFFu;
+// encodings (values of QV_ENC_* in the C ABI): Sign-Magnitude, and the two of the paper's ablation
+constexpr int ENC_SM = 0, ENC_SIGN1 = 1, ENC_SQ2 = 2;
+inline int code_row_words(int nw, int encoding) { return (encoding == ENC_SIGN1 ? 1 : 2) * nw; }
+__device__ inline int code_row_words_dev(int nw, int encoding) { return (encoding == ENC_SIGN1 ? 1 : 2) * nw; }
 constexpr uint32_t QV_STATUS_NONFINITE_BIT = 1u;
 constexpr uint32_t QV_STATUS_VISITED_FULL_BIT = 2u;
 constexpr uint32_t QV_STATUS_BAD_EDGE_BIT = 4u;
 
 struct SearchParams {
     const uint32_t* adj;     // [n][R]
-    const uint64_t* codes;   // [n][2*nw]
-    const uint64_t* qcodes;  // [nq][2*nw]
+    const uint64_t* codes;   // [n][code_row_words(nw, encoding)]
+    const uint64_t* qcodes;  // [nq][code_row_words(nw, encoding)]
+    int encoding;            // ENC_*
     int64_t n;
     int64_t nq;
     int nw;                  // 64-bit words per bit-plane
@@ -49,19 +54,20 @@ struct RerankParams {
     float* scores;           // [nq][k]
 };
 
-hipError_t launch_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, hipStream_t stream);
+hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status,
+                         hipStream_t stream);
 hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
-                              int64_t npairs, int d, uint32_t* out, hipStream_t stream);
+                              int64_t npairs, int d, int encoding, uint32_t* out, hipStream_t stream);
 hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
                                hipStream_t stream);
 int64_t bq_scan_chunk_rows(int64_t n);
-hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K,
+hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, int encoding, const uint64_t* qcodes, int64_t nq, int K,
                           uint64_t* partial, uint32_t* ids, uint32_t* dist, hipStream_t stream);
 hipError_t launch_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* out,
                                hipStream_t stream);
-bool build_supports_width(int nw);
+bool build_supports_width(int nw, int encoding);
 size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch);
-hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
+hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
@@ -73,7 +79,7 @@ inline int beam_search_pool_registers(int ef) {
 }
 inline size_t beam_search_lds_bytes(int nw, uint32_t vis_slots, bool narrow, int ef) {
     return (size_t)vis_slots * (narrow ? 2 : 4) + 64 * 4 * 2 + (size_t)(64 * beam_search_pool_registers(ef) + 64) * 8 +
-           (size_t)nw * 16 + 16;
+           (size_t)nw * 24 + 16;
 }
 void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow, bool cache);
 hipError_t launch_rerank(const RerankParams& p, hipStream_t stream);

@@ -27,26 +27,55 @@ __device__ __forceinline__ void bubble_in(uint64_t (&best)[KMAX], uint64_t key) 
     }
 }
 
+// one 32-bit step of the distance under each encoding (see code_accumulate in the search kernel for the algebra):
+// c0, c1: the base row's first / second plane dword; q0, q1, q2: the query's dwords (SQ2: (hi|lo), hi, (hi&lo))
+template <int ENC>
+__device__ __forceinline__ void scan_accumulate(uint32_t c0, uint32_t c1w, uint32_t q0, uint32_t q1, uint32_t q2,
+                                                uint32_t& c1, uint32_t& c2, uint32_t& c3) {
+    if constexpr (ENC == ENC_SM) {
+        const uint32_t x = c0 ^ q0;
+        c1 += __popc(x);
+        c2 += __popc(__builtin_amdgcn_bitop3_b32(x, c1w, q1, 0xE0));   // x & (sv | sq)
+        c3 += __popc(__builtin_amdgcn_bitop3_b32(x, c1w, q1, 0x80));   // x & sv & sq
+    } else if constexpr (ENC == ENC_SIGN1) {
+        c1 += __popc(c0 ^ q0);
+    } else {
+        c1 += __popc(__builtin_amdgcn_bitop3_b32(c1w, c0, q0, 0x56));  // (hi | lo) ^ q0
+        c2 += __popc(c1w ^ q1);
+        c3 += __popc(__builtin_amdgcn_bitop3_b32(c1w, c0, q2, 0x6A));  // (hi & lo) ^ q2
+    }
+}
+
 // NW_T: 64-bit words per plane when known at compile time (query code in registers), 0: any (code in LDS)
-template <int NW_T, int KMAX>
+template <int ENC, int NW_T, int KMAX>
 __global__ __launch_bounds__(64) void bq_scan_kernel(const uint64_t* __restrict__ codes, int64_t n, int nw,
                                                      const uint64_t* __restrict__ qcodes, int64_t nq, int K,
                                                      int64_t chunk, uint64_t* __restrict__ partial) {
-    extern __shared__ uint32_t qlds[];  // generic path: [4*nw][64] dwords, word-major
+    extern __shared__ uint32_t qlds[];  // generic path: [6*nw][64] dwords, word-major
     const int lane = threadIdx.x;
     const int64_t qi = (int64_t)blockIdx.x * 64 + lane;
     const bool live = qi < nq;
     const int NW = NW_T > 0 ? NW_T : nw;
     const int DW = 2 * NW;  // dwords per plane
     constexpr int DW_T = NW_T > 0 ? 2 * NW_T : 1;
-    uint32_t qp[DW_T], qs[DW_T];
-    const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(qcodes + (live ? qi : 0) * (int64_t)(2 * NW));
+    constexpr int PLANES = ENC == ENC_SIGN1 ? 1 : 2;
+    uint32_t qp[DW_T], qs[DW_T], q3[DW_T];
+    const uint32_t* qsrc = reinterpret_cast<const uint32_t*>(qcodes + (live ? qi : 0) * (int64_t)(PLANES * NW));
+    auto prepare = [&](int w, uint32_t& q0, uint32_t& q1, uint32_t& q2) {
+        const uint32_t a = qsrc[w], b = PLANES == 2 ? qsrc[DW + w] : 0u;
+        if constexpr (ENC == ENC_SQ2) { q0 = a | b; q1 = b; q2 = a & b; }
+        else { q0 = a; q1 = b; q2 = 0u; }
+    };
     if constexpr (NW_T > 0) {
 #pragma unroll
-        for (int w = 0; w < DW_T; ++w) { qp[w] = qsrc[w]; qs[w] = qsrc[DW_T + w]; }
+        for (int w = 0; w < DW_T; ++w) prepare(w, qp[w], qs[w], q3[w]);
     } else {
-        for (int w = 0; w < 2 * DW; ++w) qlds[w * 64 + lane] = qsrc[w];
-        qp[0] = qs[0] = 0;
+        for (int w = 0; w < DW; ++w) {
+            uint32_t q0, q1, q2;
+            prepare(w, q0, q1, q2);
+            qlds[w * 64 + lane] = q0; qlds[(DW + w) * 64 + lane] = q1; qlds[(2 * DW + w) * 64 + lane] = q2;
+        }
+        qp[0] = qs[0] = q3[0] = 0;
     }
     uint64_t best[KMAX];
 #pragma unroll
@@ -56,25 +85,18 @@ __global__ __launch_bounds__(64) void bq_scan_kernel(const uint64_t* __restrict_
     const int64_t lo = (int64_t)blockIdx.y * chunk;
     const int64_t hi = lo + chunk < n ? lo + chunk : n;
     for (int64_t row = lo; row < hi; ++row) {
-        const uint32_t* c = reinterpret_cast<const uint32_t*>(codes + row * (int64_t)(2 * NW));  // wave-uniform
+        const uint32_t* c = reinterpret_cast<const uint32_t*>(codes + row * (int64_t)(PLANES * NW));  // wave-uniform
         uint32_t c1 = 0, c2 = 0, c3 = 0;
         if constexpr (NW_T > 0) {
 #pragma unroll
-            for (int w = 0; w < DW_T; ++w) {
-                const uint32_t x = c[w] ^ qp[w], sv = c[DW_T + w];
-                c1 += __popc(x);
-                c2 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, qs[w], 0xE0));   // x & (sv | sq)
-                c3 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, qs[w], 0x80));   // x & sv & sq
-            }
+            for (int w = 0; w < DW_T; ++w)
+                scan_accumulate<ENC>(c[w], PLANES == 2 ? c[DW_T + w] : 0u, qp[w], qs[w], q3[w], c1, c2, c3);
         } else {
-            for (int w = 0; w < DW; ++w) {
-                const uint32_t x = c[w] ^ qlds[w * 64 + lane], sv = c[DW + w], sq = qlds[(DW + w) * 64 + lane];
-                c1 += __popc(x);
-                c2 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, sq, 0xE0));
-                c3 += __popc(__builtin_amdgcn_bitop3_b32(x, sv, sq, 0x80));
-            }
+            for (int w = 0; w < DW; ++w)
+                scan_accumulate<ENC>(c[w], PLANES == 2 ? c[DW + w] : 0u, qlds[w * 64 + lane], qlds[(DW + w) * 64 + lane],
+                                     qlds[(2 * DW + w) * 64 + lane], c1, c2, c3);
         }
-        const uint64_t key = ((uint64_t)(c1 + c2 + 2u * c3) << 32) | (uint32_t)row;
+        const uint64_t key = ((uint64_t)(ENC == ENC_SM ? c1 + c2 + 2u * c3 : c1 + c2 + c3) << 32) | (uint32_t)row;
         if (key < worst) {
             bubble_in<KMAX>(best, key);
 #pragma unroll
@@ -150,13 +172,13 @@ int64_t bq_scan_chunk_rows(int64_t n) {
     return chunk;
 }
 
-template <int NW_T>
+template <int ENC, int NW_T>
 static hipError_t launch_scan_k(const uint64_t* codes, int64_t n, int nw, const uint64_t* qcodes, int64_t nq, int K,
                                 int64_t chunk, uint64_t* partial, hipStream_t stream) {
     dim3 grid((unsigned)((nq + 63) / 64), (unsigned)((n + chunk - 1) / chunk));
-    size_t lds = NW_T > 0 ? 0 : (size_t)nw * 4 * 64 * 4;
+    size_t lds = NW_T > 0 ? 0 : (size_t)nw * 6 * 64 * 4;
     if (K <= 16) {
-        auto kern = bq_scan_kernel<NW_T, 16>;
+        auto kern = bq_scan_kernel<ENC, NW_T, 16>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -164,7 +186,7 @@ static hipError_t launch_scan_k(const uint64_t* codes, int64_t n, int nw, const 
         }
         hipLaunchKernelGGL(kern, grid, dim3(64), lds, stream, codes, n, nw, qcodes, nq, K, chunk, partial);
     } else {
-        auto kern = bq_scan_kernel<NW_T, 64>;
+        auto kern = bq_scan_kernel<ENC, NW_T, 64>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -175,21 +197,29 @@ static hipError_t launch_scan_k(const uint64_t* codes, int64_t n, int nw, const 
     return hipGetLastError();
 }
 
-hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, const uint64_t* qcodes, int64_t nq, int K,
+hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, int encoding, const uint64_t* qcodes, int64_t nq, int K,
                           uint64_t* partial, uint32_t* ids, uint32_t* dist, hipStream_t stream) {
     if (nq == 0) return hipSuccess;
     const int nw = (d + 63) / 64;
     const int64_t chunk = bq_scan_chunk_rows(n);
     const int nchunks = n > 0 ? (int)((n + chunk - 1) / chunk) : 0;
     hipError_t e = hipSuccess;
-    if (n > 0) {
+    if (n > 0 && encoding == ENC_SIGN1) {
+        e = nw == 12 ? launch_scan_k<ENC_SIGN1, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream)
+                     : launch_scan_k<ENC_SIGN1, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream);
+        if (e != hipSuccess) return e;
+    } else if (n > 0 && encoding == ENC_SQ2) {
+        e = nw == 12 ? launch_scan_k<ENC_SQ2, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream)
+                     : launch_scan_k<ENC_SQ2, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream);
+        if (e != hipSuccess) return e;
+    } else if (n > 0) {
         switch (nw) {
-            case 2: e = launch_scan_k<2>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 6: e = launch_scan_k<6>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 8: e = launch_scan_k<8>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 12: e = launch_scan_k<12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 16: e = launch_scan_k<16>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            default: e = launch_scan_k<0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+            case 2: e = launch_scan_k<ENC_SM, 2>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+            case 6: e = launch_scan_k<ENC_SM, 6>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+            case 8: e = launch_scan_k<ENC_SM, 8>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+            case 12: e = launch_scan_k<ENC_SM, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+            case 16: e = launch_scan_k<ENC_SM, 16>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+            default: e = launch_scan_k<ENC_SM, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
         }
         if (e != hipSuccess) return e;
     }

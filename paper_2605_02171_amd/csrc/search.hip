@@ -62,6 +62,46 @@ __device__ __forceinline__ void sm_accumulate(uint64_t pv, uint64_t sv, uint64_t
     c3 += __popc(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0x80)) + __popc(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0x80));
 }
 
+// The same step for any of the three encodings (ENC_SM: the method; ENC_SIGN1, ENC_SQ2: the two of the
+// paper's ablation, Sec. 5.4 / Table 10).  w0, w1: the node's first and second bit-plane word; q0, q1,
+// q2: the query's words as code_query_words() prepared them.
+//   ENC_SIGN1  distance = pc(sign_v xor sign_q)                                  (w1, q1, q2 unused)
+//   ENC_SQ2    level = 2*hi + lo; |level_v - level_q| = sum over k = 1..3 of [level_v >= k] xor [level_q >= k];
+//              [level >= 1] = hi|lo, [level >= 2] = hi, [level >= 3] = hi&lo.  With w0 = lo, w1 = hi and
+//              q0 = (hi|lo)_q, q1 = hi_q, q2 = (hi&lo)_q: three popcounts, the first and third of a single
+//              three-input operation each (truth tables 0x56 = (a|b)^c, 0x6A = (a&b)^c).
+template <int ENC>
+__device__ __forceinline__ void code_accumulate(uint64_t w0, uint64_t w1, uint64_t q0, uint64_t q1, uint64_t q2,
+                                                uint32_t& c1, uint32_t& c2, uint32_t& c3) {
+    if constexpr (ENC == ENC_SM) {
+        sm_accumulate(w0, w1, q0, q1, c1, c2, c3);
+    } else if constexpr (ENC == ENC_SIGN1) {
+        c1 += __popcll(w0 ^ q0);
+    } else {
+        const uint32_t ll = (uint32_t)w0, lh = (uint32_t)(w0 >> 32), hl = (uint32_t)w1, hh = (uint32_t)(w1 >> 32);
+        c1 += __popc(__builtin_amdgcn_bitop3_b32(hl, ll, (uint32_t)q0, 0x56)) +
+              __popc(__builtin_amdgcn_bitop3_b32(hh, lh, (uint32_t)(q0 >> 32), 0x56));
+        c2 += __popcll(w1 ^ q1);
+        c3 += __popc(__builtin_amdgcn_bitop3_b32(hl, ll, (uint32_t)q2, 0x6A)) +
+              __popc(__builtin_amdgcn_bitop3_b32(hh, lh, (uint32_t)(q2 >> 32), 0x6A));
+    }
+}
+
+template <int ENC>
+__device__ __forceinline__ uint32_t code_distance_from_counts(uint32_t c1, uint32_t c2, uint32_t c3) {
+    return ENC == ENC_SM ? c1 + c2 + 2u * c3 : c1 + c2 + c3;
+}
+
+// query words as code_accumulate() wants them, from the two plane words of the query's own code
+template <int ENC>
+__device__ __forceinline__ void code_query_words(uint64_t a, uint64_t b, uint64_t& q0, uint64_t& q1, uint64_t& q2) {
+    if constexpr (ENC == ENC_SQ2) {
+        q0 = a | b; q1 = b; q2 = a & b;
+    } else {
+        q0 = a; q1 = b; q2 = 0;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Visited set, 32-bit entries: buckets of four ids; an id lives in the first bucket, counting from
 // its home bucket, that had a free slot when it arrived.  Slots are never freed, so a lookup may
@@ -325,7 +365,7 @@ __device__ __forceinline__ void merge_new_keys_wide(Pool<P>& pool, uint64_t mine
     pool.size = new_size;
 }
 
-template <int NW_T, int G, int P, bool NARROW>
+template <int ENC, int NW_T, int G, int P, bool NARROW>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
     const int lane = threadIdx.x;
@@ -343,7 +383,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     uint32_t* list = tab + tab_words;  // [64] compacted new neighbour ids
     uint32_t* dlist = list + 64;       // [64] their distances (generic gather path)
     uint64_t* skeys = reinterpret_cast<uint64_t*>(dlist + 64);  // [64*P + 64] merge scatter area
-    uint64_t* qlds = skeys + 64 * P + 64;                      // [2*NW] query code (generic path)
+    uint64_t* qlds = skeys + 64 * P + 64;                      // [3*NW] query words (generic path)
 
     for (uint32_t i = lane * 4; i < tab_words; i += 256)
         *reinterpret_cast<uint4*>(tab + i) = make_uint4(EMPTY_ID, EMPTY_ID, EMPTY_ID, EMPTY_ID);
@@ -360,18 +400,25 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     // in one 16-byte load
     constexpr bool BLOCKED = QUAD_REDUCE && NW_T % (2 * G) == 0;
     const int sub = lane % G, grp = lane / G;
-    const uint64_t* qsrc = p.qcodes + q * (int64_t)(2 * NW);
-    uint64_t qp[KW], qs[KW];
+    constexpr int PLANES = ENC == ENC_SIGN1 ? 1 : 2;
+    const int RW = PLANES * NW;  // 64-bit words per code row
+    const uint64_t* qsrc = p.qcodes + q * (int64_t)RW;
+    uint64_t qp[KW], qs[KW], q3[KW];
     if constexpr (NW_T > 0) {
 #pragma unroll
         for (int i = 0; i < KW; ++i) {
             int w = BLOCKED ? sub * KW + i : sub + i * G;
-            qp[i] = w < NW_T ? qsrc[w] : 0ull;
-            qs[i] = w < NW_T ? qsrc[NW_T + w] : 0ull;
+            const uint64_t a = w < NW_T ? qsrc[w] : 0ull;
+            const uint64_t b = (PLANES == 2 && w < NW_T) ? qsrc[NW_T + w] : 0ull;
+            code_query_words<ENC>(a, b, qp[i], qs[i], q3[i]);
         }
     } else {
-        for (int w = lane; w < 2 * NW; w += 64) qlds[w] = qsrc[w];
-        qp[0] = qs[0] = 0;
+        for (int w = lane; w < NW; w += 64) {
+            uint64_t q0, q1, q2;
+            code_query_words<ENC>(qsrc[w], PLANES == 2 ? qsrc[NW + w] : 0ull, q0, q1, q2);
+            qlds[w] = q0; qlds[NW + w] = q1; qlds[2 * NW + w] = q2;
+        }
+        qp[0] = qs[0] = q3[0] = 0;
     }
 
     Pool<P> pool;
@@ -396,24 +443,29 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             for (int b = 0; b < G; ++b) {
                 const int ri = b * RPP + grp;
                 if (ri < m) {
-                    const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW_T);
+                    const uint64_t* row = p.codes + (int64_t)list[ri] * (PLANES * NW_T);
                     if constexpr (BLOCKED) {
                         const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
                         const uint4* m4 = reinterpret_cast<const uint4*>(row + NW_T + sub * KW);
 #pragma unroll
                         for (int i = 0; i < KW / 2; ++i) {
-                            const uint4 a = r4[i], c = m4[i];
+                            const uint4 a = r4[i];
                             pv[b][2 * i] = ((uint64_t)a.y << 32) | a.x;
                             pv[b][2 * i + 1] = ((uint64_t)a.w << 32) | a.z;
-                            sv[b][2 * i] = ((uint64_t)c.y << 32) | c.x;
-                            sv[b][2 * i + 1] = ((uint64_t)c.w << 32) | c.z;
+                            if constexpr (PLANES == 2) {
+                                const uint4 c = m4[i];
+                                sv[b][2 * i] = ((uint64_t)c.y << 32) | c.x;
+                                sv[b][2 * i + 1] = ((uint64_t)c.w << 32) | c.z;
+                            } else {
+                                sv[b][2 * i] = sv[b][2 * i + 1] = 0ull;
+                            }
                         }
                     } else {
 #pragma unroll
                         for (int i = 0; i < KW; ++i) {
                             int w = sub + i * G;
                             pv[b][i] = w < NW_T ? row[w] : 0ull;
-                            sv[b][i] = w < NW_T ? row[NW_T + w] : 0ull;
+                            sv[b][i] = (PLANES == 2 && w < NW_T) ? row[NW_T + w] : 0ull;
                         }
                     }
                 } else {
@@ -428,10 +480,10 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                 if (b * RPP < m) {  // wave-uniform
 #pragma unroll
                     for (int i = 0; i < KW; ++i) {
-                        sm_accumulate(pv[b][i], sv[b][i], qp[i], qs[i], c1, c2, c3);
+                        code_accumulate<ENC>(pv[b][i], sv[b][i], qp[i], qs[i], q3[i], c1, c2, c3);
                     }
                 }
-                part[b] = c1 + c2 + 2u * c3;
+                part[b] = code_distance_from_counts<ENC>(c1, c2, c3);
             }
             // reduce-scatter: afterwards lane `sub` holds the full sum of pass my_b
             uint32_t dist;
@@ -460,12 +512,12 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     for (int b = 0; b < BATCH; ++b) {
                         int ri = base + b * RPP + grp;
                         if (ri < m) {
-                            const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW_T);
+                            const uint64_t* row = p.codes + (int64_t)list[ri] * (PLANES * NW_T);
 #pragma unroll
                             for (int i = 0; i < KW; ++i) {
                                 int w = sub + i * G;
                                 pv[b][i] = w < NW_T ? row[w] : 0ull;
-                                sv[b][i] = w < NW_T ? row[NW_T + w] : 0ull;
+                                sv[b][i] = (PLANES == 2 && w < NW_T) ? row[NW_T + w] : 0ull;
                             }
                         } else {
 #pragma unroll
@@ -479,9 +531,9 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                             uint32_t c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
                             for (int i = 0; i < KW; ++i) {
-                                sm_accumulate(pv[b][i], sv[b][i], qp[i], qs[i], c1, c2, c3);
+                                code_accumulate<ENC>(pv[b][i], sv[b][i], qp[i], qs[i], q3[i], c1, c2, c3);
                             }
-                            uint32_t dist = c1 + c2 + 2u * c3;
+                            uint32_t dist = code_distance_from_counts<ENC>(c1, c2, c3);
 #pragma unroll
                             for (int off = G >> 1; off >= 1; off >>= 1) dist += __shfl_xor((int)dist, off);
                             if (sub == 0 && ri < m) dlist[ri] = dist;
@@ -493,12 +545,13 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     int ri = base + grp;
                     uint32_t c1 = 0, c2 = 0, c3 = 0;
                     if (ri < m) {
-                        const uint64_t* row = p.codes + (int64_t)list[ri] * (2 * NW);
+                        const uint64_t* row = p.codes + (int64_t)list[ri] * RW;
                         for (int w = sub; w < NW; w += G) {
-                            sm_accumulate(row[w], row[NW + w], qlds[w], qlds[NW + w], c1, c2, c3);
+                            code_accumulate<ENC>(row[w], PLANES == 2 ? row[NW + w] : 0ull, qlds[w], qlds[NW + w],
+                                                 qlds[2 * NW + w], c1, c2, c3);
                         }
                     }
-                    uint32_t dist = c1 + c2 + 2u * c3;
+                    uint32_t dist = code_distance_from_counts<ENC>(c1, c2, c3);
 #pragma unroll
                     for (int off = G >> 1; off >= 1; off >>= 1) dist += __shfl_xor((int)dist, off);
                     if (sub == 0 && ri < m) dlist[ri] = dist;
@@ -636,10 +689,10 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     }
 }
 
-template <int NW_T, int G, int P, bool NARROW>
+template <int ENC, int NW_T, int G, int P, bool NARROW>
 static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
     size_t lds = beam_search_lds_bytes(p.nw, p.vis_slots, NARROW, p.ef);
-    auto kern = beam_search_kernel<NW_T, G, P, NARROW>;
+    auto kern = beam_search_kernel<ENC, NW_T, G, P, NARROW>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -649,34 +702,34 @@ static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int NW_T, int G, int P>
+template <int ENC, int NW_T, int G, int P>
 static hipError_t launch_n(const SearchParams& p, hipStream_t stream) {
-    return p.vis_regions > 0 ? launch_one<NW_T, G, P, true>(p, stream) : launch_one<NW_T, G, P, false>(p, stream);
+    return p.vis_regions > 0 ? launch_one<ENC, NW_T, G, P, true>(p, stream) : launch_one<ENC, NW_T, G, P, false>(p, stream);
 }
 
-template <int NW_T, int G>
+template <int ENC, int NW_T, int G>
 static hipError_t launch_p(const SearchParams& p, hipStream_t stream) {
     int P = (p.ef + 63) / 64;
-    if (P <= 1) return launch_n<NW_T, G, 1>(p, stream);
-    if (P <= 2) return launch_n<NW_T, G, 2>(p, stream);
-    if (P <= 4) return launch_n<NW_T, G, 4>(p, stream);
-    if (P <= 8) return launch_n<NW_T, G, 8>(p, stream);
-    return launch_n<NW_T, G, 16>(p, stream);
+    if (P <= 1) return launch_n<ENC, NW_T, G, 1>(p, stream);
+    if (P <= 2) return launch_n<ENC, NW_T, G, 2>(p, stream);
+    if (P <= 4) return launch_n<ENC, NW_T, G, 4>(p, stream);
+    if (P <= 8) return launch_n<ENC, NW_T, G, 8>(p, stream);
+    return launch_n<ENC, NW_T, G, 16>(p, stream);
 }
 
-template <int NW_T>
+template <int ENC, int NW_T>
 static hipError_t launch_g(const SearchParams& p, int g, hipStream_t stream) {
     switch (g) {
-        case 1: return launch_p<NW_T, 1>(p, stream);
-        case 2: return launch_p<NW_T, 2>(p, stream);
-        case 4: return launch_p<NW_T, 4>(p, stream);
-        case 8: return launch_p<NW_T, 8>(p, stream);
-        case 16: return launch_p<NW_T, 16>(p, stream);
+        case 1: return launch_p<ENC, NW_T, 1>(p, stream);
+        case 2: return launch_p<ENC, NW_T, 2>(p, stream);
+        case 4: return launch_p<ENC, NW_T, 4>(p, stream);
+        case 8: return launch_p<ENC, NW_T, 8>(p, stream);
+        case 16: return launch_p<ENC, NW_T, 16>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }
 
-#if QV_SEARCH_WIDTH == 0
+#if QV_SEARCH_WIDTH == 0 && QV_SEARCH_ENC == 0
 static int default_lanes_per_row(int nw) {
     if (nw <= 12) return 2;
     if (nw <= 24) return 4;
@@ -709,41 +762,43 @@ void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow, bool
 
 #endif
 
-// This file is compiled once per code width (-DQV_SEARCH_WIDTH=w, w = 64-bit words per bit-plane, 0 =
-// any width at run time), so that the instantiations build in parallel; each object exports
-// launch_beam_search_w<w>, and the object for width 0 also holds the dispatcher and the table planner.
-#ifndef QV_SEARCH_WIDTH
-#error "compile with -DQV_SEARCH_WIDTH=<words per plane> (see build.py)"
+// This file is compiled once per (encoding, code width) pair (-DQV_SEARCH_ENC=e -DQV_SEARCH_WIDTH=w, w = 64-bit
+// words per bit-plane, 0 = any width at run time), so that the instantiations build in parallel; each
+// object exports launch_beam_search_w<e, w>, and the object for (ENC_SM, 0) also holds the dispatcher and the
+// table planner.  The ablation encodings exist for the widths 12 (768-d, the paper's ablation) and 0.
+#if !defined(QV_SEARCH_WIDTH) || !defined(QV_SEARCH_ENC)
+#error "compile with -DQV_SEARCH_ENC=<encoding> -DQV_SEARCH_WIDTH=<words per plane> (see build.py)"
 #endif
 
-template <int NW_T>
+template <int ENC, int NW_T>
 hipError_t launch_beam_search_w(const SearchParams& p, int g, hipStream_t stream) {
-    return launch_g<NW_T>(p, g, stream);
+    return launch_g<ENC, NW_T>(p, g, stream);
 }
-template hipError_t launch_beam_search_w<QV_SEARCH_WIDTH>(const SearchParams& p, int g, hipStream_t stream);
+template hipError_t launch_beam_search_w<QV_SEARCH_ENC, QV_SEARCH_WIDTH>(const SearchParams& p, int g, hipStream_t stream);
 
-#if QV_SEARCH_WIDTH == 0
-extern template hipError_t launch_beam_search_w<2>(const SearchParams&, int, hipStream_t);
-extern template hipError_t launch_beam_search_w<6>(const SearchParams&, int, hipStream_t);
-extern template hipError_t launch_beam_search_w<8>(const SearchParams&, int, hipStream_t);
-extern template hipError_t launch_beam_search_w<12>(const SearchParams&, int, hipStream_t);
-extern template hipError_t launch_beam_search_w<16>(const SearchParams&, int, hipStream_t);
-extern template hipError_t launch_beam_search_w<24>(const SearchParams&, int, hipStream_t);
-extern template hipError_t launch_beam_search_w<48>(const SearchParams&, int, hipStream_t);
+#if QV_SEARCH_WIDTH == 0 && QV_SEARCH_ENC == 0
+#define QV_EXT(E, W) extern template hipError_t launch_beam_search_w<E, W>(const SearchParams&, int, hipStream_t);
+QV_EXT(ENC_SM, 2) QV_EXT(ENC_SM, 6) QV_EXT(ENC_SM, 8) QV_EXT(ENC_SM, 12) QV_EXT(ENC_SM, 16) QV_EXT(ENC_SM, 24) QV_EXT(ENC_SM, 48)
+QV_EXT(ENC_SIGN1, 0) QV_EXT(ENC_SIGN1, 12) QV_EXT(ENC_SQ2, 0) QV_EXT(ENC_SQ2, 12)
+#undef QV_EXT
 
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream) {
     if (p.nq == 0) return hipSuccess;
     int g = lanes_per_row > 0 ? lanes_per_row : default_lanes_per_row(p.nw);
     if (g > 16) g = 16;
+    if (p.encoding == ENC_SIGN1)
+        return p.nw == 12 ? launch_beam_search_w<ENC_SIGN1, 12>(p, g, stream) : launch_beam_search_w<ENC_SIGN1, 0>(p, g, stream);
+    if (p.encoding == ENC_SQ2)
+        return p.nw == 12 ? launch_beam_search_w<ENC_SQ2, 12>(p, g, stream) : launch_beam_search_w<ENC_SQ2, 0>(p, g, stream);
     switch (p.nw) {
-        case 2: return launch_beam_search_w<2>(p, g, stream);
-        case 6: return launch_beam_search_w<6>(p, g, stream);
-        case 8: return launch_beam_search_w<8>(p, g, stream);
-        case 12: return launch_beam_search_w<12>(p, g, stream);
-        case 16: return launch_beam_search_w<16>(p, g, stream);
-        case 24: return launch_beam_search_w<24>(p, g, stream);
-        case 48: return launch_beam_search_w<48>(p, g, stream);
-        default: return launch_beam_search_w<0>(p, g, stream);
+        case 2: return launch_beam_search_w<ENC_SM, 2>(p, g, stream);
+        case 6: return launch_beam_search_w<ENC_SM, 6>(p, g, stream);
+        case 8: return launch_beam_search_w<ENC_SM, 8>(p, g, stream);
+        case 12: return launch_beam_search_w<ENC_SM, 12>(p, g, stream);
+        case 16: return launch_beam_search_w<ENC_SM, 16>(p, g, stream);
+        case 24: return launch_beam_search_w<ENC_SM, 24>(p, g, stream);
+        case 48: return launch_beam_search_w<ENC_SM, 48>(p, g, stream);
+        default: return launch_beam_search_w<ENC_SM, 0>(p, g, stream);
     }
 }
 #endif
