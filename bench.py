@@ -67,6 +67,9 @@ def main() -> int:
                     help="host: the input graph comes from the host generator (default; the only choice the CPU "
                          "oracle leg accepts); gpu: built by qv_build_graph (no CPU leg: nothing the library "
                          "produced is ever an oracle input)")
+    ap.add_argument("--encoding", choices=("sm", "sign1", "sq2"), default="sm",
+                    help="sm: the method; sign1 / sq2: the paper's ablation encodings (graph built on the GPU in that "
+                         "encoding's own distance, so --graph gpu is implied and there is no CPU leg)")
     ap.add_argument("--cold-host", action="store_true",
                     help="keep the float32 vectors in pinned host memory (rerank reads them over PCIe)")
     ap.add_argument("--no-scan", action="store_true", help="skip the brute-force code scan / overlap probe")
@@ -84,6 +87,9 @@ def main() -> int:
     from workloads import datagen, graph
 
     torch.cuda.set_device(0)
+    enc = {"sm": qv.ENC_SM, "sign1": qv.ENC_SIGN1, "sq2": qv.ENC_SQ2}[args.encoding]
+    if enc != qv.ENC_SM:
+        args.graph = "gpu"
     w = datagen.scaled(args.workload, n=args.n or None, nq=args.nq or None)
     ef, k = args.ef, w.k
     t0 = time.time()
@@ -102,13 +108,13 @@ def main() -> int:
         # entry = the node whose code is nearest to the code of the float32 centroid (ties: smallest id), as the
         # host generator picks it; graph by the library's own construction
         args.cpu_sample = 0
-        c0 = qv.encode(xd)
+        c0 = qv.encode(xd, enc=enc)
         cen = torch.zeros((1, w.d), dtype=torch.float64, device="cuda")
         for s0 in range(0, w.n, 1 << 18):
             cen += xd[s0:s0 + (1 << 18)].sum(0, keepdim=True, dtype=torch.float64)
-        eid, _ = qv.bq_scan(c0, qv.encode((cen / w.n).float()), w.d, 1)
+        eid, _ = qv.bq_scan(c0, qv.encode((cen / w.n).float(), enc=enc), w.d, 1, enc=enc)
         entry = int(qv.to_numpy_u32(eid)[0, 0])
-        adjd = qv.build_graph(c0, w.d, w.R, w.L, w.alpha, entry)
+        adjd = qv.build_graph(c0, w.d, w.R, w.L, w.alpha, entry, enc=enc)
         torch.cuda.synchronize()
         adj = None
         del c0
@@ -117,23 +123,23 @@ def main() -> int:
         f"({'host, %d threads' % graph.host_threads() if args.graph == 'host' else 'GPU, entry %d' % entry})")
 
     # base encode (index-build side of the hot path): timed on its own
-    codes = qv.encode(xd)
+    codes = qv.encode(xd, enc=enc)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(5):
-        codes = qv.encode(xd)
+        codes = qv.encode(xd, enc=enc)
     e1.record()
     torch.cuda.synchronize()
     enc_ms = e0.elapsed_time(e1) / 5
-    enc_bytes = w.n * (4 * w.d + w.d // 4)
+    enc_bytes = w.n * (4 * w.d + 8 * qv.code_words(w.d, enc))
     log(f"encode base: {enc_ms:.3f} ms, {enc_bytes / enc_ms / 1e6:.0f} GB/s")
 
     x_cold = None
     if args.cold_host:
         x_cold = torch.empty(x.shape, dtype=torch.float32, pin_memory=True)
         x_cold.copy_(torch.from_numpy(x))
-    index = qv.Index(adjd, codes, x_cold if args.cold_host else xd, entry)
+    index = qv.Index(adjd, codes, x_cold if args.cold_host else xd, entry, enc=enc)
     ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
 
     # Counters for the algorithmic-byte model: one traced pass with the visited set that never forgets, which
@@ -155,7 +161,7 @@ def main() -> int:
     status = qv.to_numpy_u32(traced.status)
     ids_gpu = qv.to_numpy_u32(traced.ids)
     assert (qv.to_numpy_u32(traced.n_expanded) == n_exp).all()
-    code_b = w.d // 4 if w.d % 64 == 0 else 16 * ((w.d + 63) // 64)
+    code_b = 8 * qv.code_words(w.d, enc)
     search_bytes = int(4 * w.R * n_exp.sum() + code_b * n_eval.sum() + code_b * w.nq + 8 * ef * w.nq)
     rerank_bytes = int(4 * w.d * n_cand.sum() + 4 * w.d * w.nq + 8 * k * w.nq)
     encq_bytes = int(w.nq * (4 * w.d + code_b))
@@ -189,7 +195,7 @@ def main() -> int:
     # batch evaluates, no arithmetic
     gather_gbps = None
     n_rows = int(n_eval.sum()) // 64 * 64
-    if n_rows >= 64:
+    if n_rows >= 64 and enc == qv.ENC_SM:      # the probe reads rows of two planes
         rid = torch.randint(0, w.n, (n_rows,), device="cuda", dtype=torch.int32)
         qv.gather_probe(codes, w.d, rid)
         torch.cuda.synchronize()
@@ -218,19 +224,20 @@ def main() -> int:
     # brute-force scan in code space (all queries x all base codes) and the overlap probe against exact top-10
     scan = None
     if not args.no_scan:
-        qcodes_d = qv.encode(qd)
-        sid, sdist = qv.bq_scan(codes, qcodes_d, w.d, k)
+        qcodes_d = qv.encode(qd, enc=enc)
+        sid, sdist = qv.bq_scan(codes, qcodes_d, w.d, k, enc=enc)
         torch.cuda.synchronize()
         s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         s0.record()
-        sid, sdist = qv.bq_scan(codes, qcodes_d, w.d, k)
+        sid, sdist = qv.bq_scan(codes, qcodes_d, w.d, k, enc=enc)
         s1.record()
         torch.cuda.synchronize()
         scan_ms = s0.elapsed_time(s1)
         hits = qv.topk_overlap(sid, torch.from_numpy(gt.astype(np.uint32).view(np.int32)).cuda())
         overlap = float(qv.to_numpy_u32(hits).sum()) / (w.nq * k)
         found = qv.topk_overlap(sid, qv.from_numpy_u32(np.ascontiguousarray(qv.to_numpy_u32(traced.cand_ids)[:, :k])))
-        lane_ops = 6.0 * 2 * ((w.d + 31) // 32) / 2 * w.nq * w.n   # xor, 2 three-input ops, 3 popcount-adds per 32 dims
+        # per 32 dims: xor, 2 three-input ops, 3 popcount-adds (2-bit encodings); xor + popcount-add (1-bit sign)
+        lane_ops = (2.0 if enc == qv.ENC_SIGN1 else 6.0) * ((w.d + 31) // 32) * w.nq * w.n
         alu_peak = 256 * 64 * 2.4e9
         scan = {"ms": scan_ms, "dist_evals_per_s": w.nq * w.n / (scan_ms * 1e-3),
                 "top10_overlap_code_vs_exact": overlap,
@@ -245,13 +252,13 @@ def main() -> int:
     # graph construction on the GPU (same reading as the oracle's orc_build_graph), timed, then searched
     gpu_build = None
     if args.gpu_build:
-        adj_g = qv.build_graph(codes, w.d, w.R, w.L, w.alpha, entry)      # warm-up (first launches, allocator)
+        adj_g = qv.build_graph(codes, w.d, w.R, w.L, w.alpha, entry, enc=enc)      # warm-up (first launches, allocator)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        adj_g = qv.build_graph(codes, w.d, w.R, w.L, w.alpha, entry)
+        adj_g = qv.build_graph(codes, w.d, w.R, w.L, w.alpha, entry, enc=enc)
         torch.cuda.synchronize()
         t_gb = time.perf_counter() - t0
-        index_g = qv.Index(adj_g, codes, xd, entry)
+        index_g = qv.Index(adj_g, codes, xd, entry, enc=enc)
         og = qv.search(index_g, qd, k, ef, workspace=ws)
         torch.cuda.synchronize()
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -327,7 +334,7 @@ def main() -> int:
                                        "rerank": rerank_bytes},
         "whole_path_GBps": (encq_bytes + search_bytes + rerank_bytes) / (ms_per_step * 1e-3) / 1e9,
         "encode_base": {"ms": enc_ms, "GBps": enc_bytes / enc_ms / 1e6},
-        "graph_build_s": t_graph, "graph_from": args.graph,
+        "graph_build_s": t_graph, "graph_from": args.graph, "encoding": args.encoding,
         "random_row_gather_ceiling_GBps": gather_gbps,
         "search_bytes_line_granular": int(4 * w.R * n_exp.sum() + (2 * 128 if code_b % 128 else code_b) * n_eval.sum())
         if code_b <= 256 else None,
