@@ -106,17 +106,32 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float*
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
     const int64_t stride = (int64_t)gridDim.x * ENC_WAVES;
-    // grid-stride over vectors: the grid is sized to fill the chip a few times, not one wave per vector
-    for (int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv; v < n; v += stride) {
+    // grid-stride over vectors: the grid is sized to fill the chip a few times, not one wave per vector.
+    // The next vector of this wave is loaded while the current one is processed, so a wave always has a
+    // row of loads in flight.
+    auto load_row = [&](int64_t v, auto& dst) {
         const float* xv = x + v * (int64_t)d;
-        uint64_t* cv = codes + v * (int64_t)(2 * W);
-
-        float xr[W];
 #pragma unroll
         for (int w = 0; w < W; ++w) {
             int i = (w << 6) + lane;
-            xr[w] = i < d ? xv[i] : 0.0f;
+            dst[w] = (v < n && i < d) ? xv[i] : 0.0f;
         }
+    };
+    constexpr bool PIPELINED = W <= 16;  // longer rows are enough bytes in flight by themselves
+    int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv;
+    float xr[W], xnext[PIPELINED ? W : 1];
+    if constexpr (PIPELINED) load_row(v, xnext);
+    for (; v < n; v += stride) {
+        const float* xv = x + v * (int64_t)d;
+        uint64_t* cv = codes + v * (int64_t)(2 * W);
+        if constexpr (PIPELINED) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) xr[w] = xnext[w];
+            load_row(v + stride, xnext);
+        } else {
+            load_row(v, xr);
+        }
+
         double part = 0.0;
         bool finite = true;
 #pragma unroll
@@ -341,7 +356,7 @@ hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_
         hipLaunchKernelGGL(encode_sq2_kernel, grid, block, 0, stream, x, n, d, codes, status);
         return hipGetLastError();
     }
-    const unsigned full = 256 * 8 * 16;  // 16 rounds of 8 workgroups per CU
+    const unsigned full = 256 * 8 * 4;  // 4 rounds of 8 workgroups per CU
     dim3 pgrid(grid.x < full ? grid.x : full);
     switch ((d + 63) / 64) {
 #define QV_ENC_CASE(W) case W: hipLaunchKernelGGL(encode_kernel_reg<W>, pgrid, block, 0, stream, x, n, d, codes, status); break;
