@@ -303,7 +303,14 @@ def main() -> int:
         t0 = time.time()
         oracle.search(q[:n1], adj, ocodes, x, entry, k, ef, threads=1)
         t_1t = time.time() - t0
+        cpu_model = "unknown"
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "unknown")
+        except OSError:
+            pass
         cpu = {"value": ns / t_cpu, "single_thread_value": n1 / t_1t, "unit": "queries/s", "cores": threads, "kind": "oracle",
+               "cpu_model": cpu_model, "host_cpus_visible": os.cpu_count(),
                "sample": f"first {ns} of the {w.nq} queries, same graph/codes/vectors; search+rerank wall time "
                          f"{t_cpu:.2f}s ({threads} threads); base encode by the oracle took {t_enc:.1f}s (not included)",
                "recall_at_10": orecall}
