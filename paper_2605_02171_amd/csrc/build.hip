@@ -243,6 +243,11 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
     if (lane < p.R) p.adj[(int64_t)b * p.R + lane] = lane < ns ? sel[lane] : EMPTY_ID;
 }
 
+__global__ void fill_empty_kernel(uint32_t* __restrict__ adj, int64_t words) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (int64_t)gridDim.x * blockDim.x)
+        adj[i] = EMPTY_ID;
+}
+
 size_t build_sort_temp_bytes(int64_t max_pairs) {
     size_t bytes = 0;
     uint64_t* none = nullptr;
@@ -320,7 +325,13 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     const size_t temp_bytes = build_sort_temp_bytes(mb * R);
     void* temp = ws;
 
-    hipError_t e = hipMemsetAsync(adj, 0xFF, (size_t)n * R * 4, stream);
+    // every slot starts empty (a kernel, not a memset node: the whole call may be captured into a graph)
+    {
+        const int64_t words = n * (int64_t)R;
+        const unsigned blocks = (unsigned)((words + 256 * 8 - 1) / (256 * 8) < 256 * 16 ? (words + 256 * 8 - 1) / (256 * 8) : 256 * 16);
+        hipLaunchKernelGGL(fill_empty_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, adj, words);
+    }
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     SearchParams sp{};
     sp.adj = adj; sp.codes = codes; sp.encoding = encoding; sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
