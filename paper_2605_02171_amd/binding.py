@@ -247,7 +247,7 @@ class Timer:
         self._h = h
 
     def read(self) -> np.ndarray:
-        """Milliseconds [calls, 3] = (query encode, beam search, rerank); waits for the events."""
+        """Milliseconds [calls, 3] = (query encode + launch-order pass, beam search kernel, rerank); waits for the events."""
         ms = np.zeros((self.max_calls, 3), dtype=np.float32)
         n = _lib.qv_timer_read(self._h, ms.ctypes.data_as(_P), self.max_calls)
         if n < 0:

@@ -26,7 +26,7 @@ int hip_fail(hipError_t e, const char* where) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t qcodes, cand_ids, cand_dist, n_cand, total;
+    size_t qcodes, cand_ids, cand_dist, n_cand, order, total;
 };
 
 WorkspaceLayout layout(int64_t nq, int d, int ef) {
@@ -36,6 +36,7 @@ WorkspaceLayout layout(int64_t nq, int d, int ef) {
     L.cand_ids = off;  off = align_up(off + (size_t)nq * ef * 4, 256);
     L.cand_dist = off; off = align_up(off + (size_t)nq * ef * 4, 256);
     L.n_cand = off;    off = align_up(off + (size_t)nq * 4, 256);
+    L.order = off;     off = align_up(off + (size_t)nq * 4, 256);
     L.total = off;
     return L;
 }
@@ -237,7 +238,6 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     // Stage 1 preamble: the query's own code
     e = qv::launch_encode(queries, nq, index->d, index->encoding, qcodes, nullptr, stream);
     if (e != hipSuccess) return hip_fail(e, "query encode launch");
-    if (ev && (e = hipEventRecord(ev[1], stream)) != hipSuccess) return hip_fail(e, "event record");
 
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes; sp.encoding = index->encoding;
@@ -266,6 +266,11 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     sp.status = trace ? trace->status : nullptr;
     sp.visit_order = trace ? trace->visit_order : nullptr;
     sp.visit_cap = trace && trace->visit_order ? trace->visit_cap : 0;
+    sp.order = nullptr;
+    if (qv::launch_query_order(sp, reinterpret_cast<uint32_t*>(ws + L.order), stream, &e))
+        sp.order = reinterpret_cast<uint32_t*>(ws + L.order);
+    if (e != hipSuccess) return hip_fail(e, "query order launch");
+    if (ev && (e = hipEventRecord(ev[1], stream)) != hipSuccess) return hip_fail(e, "event record");
     e = qv::launch_beam_search(sp, index->lanes_per_row, stream);
     if (e != hipSuccess) return hip_fail(e, "beam search launch");
     if (ev && (e = hipEventRecord(ev[2], stream)) != hipSuccess) return hip_fail(e, "event record");

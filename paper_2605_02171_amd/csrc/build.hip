@@ -337,6 +337,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     sp.adj = adj; sp.codes = codes; sp.encoding = encoding; sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
     sp.cand_ids = cand_ids; sp.cand_dist = cand_dist; sp.n_cand = n_cand;
     sp.n_expanded = nullptr; sp.n_evals = nullptr; sp.status = nullptr; sp.visit_order = nullptr; sp.visit_cap = 0;
+    sp.order = nullptr;
     plan_visited_table(sp, 4096, true, true);  // visited set as a cache: same lists, more queries per compute unit
     BuildParams bp{};
     bp.codes = codes; bp.adj = adj; bp.n = n; bp.R = R; bp.L = L; bp.alpha = alpha;

@@ -30,6 +30,7 @@ struct SearchParams {
     uint32_t vis_regions;    // > 0: 16-bit entries, table cut into this many parts ...
     uint32_t vis_region_buckets;  // ... of this many 8-tag buckets each (see plan_visited_table)
     int vis_cache;           // 0: the table never forgets an id (stops taking ids when nearly full); 1: ids displace each other
+    const uint32_t* order;   // [nq] launch order: workgroup b runs query order[b]; null: query b
     // outputs
     uint32_t* cand_ids;      // [nq][ef]
     uint32_t* cand_dist;     // [nq][ef]
@@ -71,6 +72,10 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
+// Fills order[nq] with a launch order of the queries: those whose code is farthest from the entry node's code
+// first (approximately).  Returns false (nothing launched) when the batch is too small or too large for it to
+// matter; then the caller passes no order.
+bool launch_query_order(const SearchParams& p, uint32_t* order, hipStream_t stream, hipError_t* err);
 // LDS bytes one query of the search kernel needs: visited table, two 64-entry lists, the merge scatter area
 // (64 keys per pool register of a lane, plus 64), the query code
 inline int beam_search_pool_registers(int ef) {

@@ -369,7 +369,7 @@ template <int ENC, int NW_T, int G, int P, bool NARROW>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
     const int lane = threadIdx.x;
-    const int64_t q = blockIdx.x;
+    const int64_t q = p.order ? (int64_t)p.order[blockIdx.x] : (int64_t)blockIdx.x;
     const int NW = NW_T > 0 ? NW_T : p.nw;
     const uint32_t cap = p.vis_slots;   // slots (32-bit each, or 16-bit when NARROW)
     const uint32_t vis_regions = p.vis_regions, vis_B = p.vis_region_buckets;
@@ -734,6 +734,66 @@ static int default_lanes_per_row(int nw) {
     if (nw <= 12) return 2;
     if (nw <= 24) return 4;
     return 16;
+}
+
+// Launch order.  A batch is a few rounds of resident waves deep, queries differ in length (47 to 157 expansions
+// at 1M x 768, ef = 64) and the kernel ends when the last query does, so the long ones should start first.
+// How long a query will run is not known, but it grows with the distance between the query's code and the
+// entry node's code (rank correlation 0.3-0.4 on the workloads here), which costs one distance per query.
+// Each workgroup ranks its 512 queries by that distance (farthest = rank 0, by counting) and the ranks of all
+// workgroups are interleaved: launch position = rank * workgroups + workgroup.  Workgroups hold arbitrary
+// slices of the batch, so this is the sorted order up to the difference between their quantiles, without any
+// global pass.  Only the order in which queries are picked up changes; their outputs go where they always go.
+constexpr int ORDER_BLOCK = 512;
+
+__global__ __launch_bounds__(ORDER_BLOCK) void query_order_kernel(const uint64_t* __restrict__ qcodes,
+                                                                  const uint64_t* __restrict__ codes, int64_t nq, int nw,
+                                                                  int encoding, uint32_t entry,
+                                                                  uint32_t* __restrict__ order) {
+    __shared__ uint32_t keys[ORDER_BLOCK];
+    const int tid = threadIdx.x;
+    const int64_t q = (int64_t)blockIdx.x * ORDER_BLOCK + tid;
+    uint32_t key = (uint32_t)(ORDER_BLOCK - 1 - tid);           // beyond the batch: below every real key
+    if (q < nq) {
+        const int rw = code_row_words_dev(nw, encoding);
+        const uint64_t* ce = codes + (int64_t)entry * rw;
+        const uint64_t* cq = qcodes + q * rw;
+        uint32_t c1 = 0, c2 = 0, c3 = 0;
+        for (int w = 0; w < nw; ++w) {
+            if (encoding == ENC_SIGN1) {
+                c1 += __popcll(cq[w] ^ ce[w]);
+            } else if (encoding == ENC_SQ2) {
+                const uint64_t la = cq[w], ha = cq[nw + w], lb = ce[w], hb = ce[nw + w];
+                c1 += __popcll((la | ha) ^ (lb | hb)) + __popcll((la & ha) ^ (lb & hb));
+                c2 += __popcll(ha ^ hb);
+            } else {
+                const uint64_t X = cq[w] ^ ce[w], sa = cq[nw + w], sb = ce[nw + w];
+                c1 += __popcll(X);
+                c2 += __popcll(X & (sa | sb));
+                c3 += __popcll(X & sa & sb);
+            }
+        }
+        key = ((c1 + c2 + 2u * c3 + 1u) << 9) | key;            // distances stay below 2^19, so 32 bits hold this
+    }
+    keys[tid] = key;
+    __syncthreads();
+    uint32_t rank = 0;                                          // keys are distinct: the low bits are the lane's own
+    for (int j = 0; j < ORDER_BLOCK; ++j) rank += keys[j] > key ? 1u : 0u;
+    if (q >= nq) return;
+    const int64_t blocks = gridDim.x, last_valid = nq - (blocks - 1) * ORDER_BLOCK;   // queries in the last workgroup
+    const int64_t pos = (int64_t)rank < last_valid ? (int64_t)rank * blocks + blockIdx.x
+                                                   : last_valid * blocks + ((int64_t)rank - last_valid) * (blocks - 1) + blockIdx.x;
+    order[pos] = (uint32_t)q;
+}
+
+bool launch_query_order(const SearchParams& p, uint32_t* order, hipStream_t stream, hipError_t* err) {
+    *err = hipSuccess;
+    // fewer queries than resident waves all start at once; very large batches amortise their tail
+    if (p.nq < 4096 || p.nq > (1 << 20)) return false;
+    hipLaunchKernelGGL(query_order_kernel, dim3((unsigned)((p.nq + ORDER_BLOCK - 1) / ORDER_BLOCK)), dim3(ORDER_BLOCK), 0,
+                       stream, p.qcodes, p.codes, p.nq, p.nw, p.encoding, p.entry, order);
+    *err = hipGetLastError();
+    return *err == hipSuccess;
 }
 
 // Picks the visited-table format for `slots` requested slots (rounded up to a multiple of 1024): 16-bit
