@@ -308,7 +308,7 @@ int64_t build_max_batch(int64_t n, int64_t max_batch) {
 
 size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch) {
     const int64_t mb = build_max_batch(n, max_batch);
-    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) + up256((size_t)mb * R * 8) * 2 +
+    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 8) * 2 +
            up256(build_sort_temp_bytes(mb * R)) + 256;
 }
 
@@ -320,6 +320,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     uint32_t* cand_ids = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * L * 4);
     uint32_t* cand_dist = reinterpret_cast<uint32_t*>(ws);  ws += up256((size_t)mb * L * 4);
     uint32_t* n_cand = reinterpret_cast<uint32_t*>(ws);     ws += up256((size_t)mb * 4);
+    uint32_t* order = reinterpret_cast<uint32_t*>(ws);      ws += up256((size_t)mb * 4);
     uint64_t* pairs = reinterpret_cast<uint64_t*>(ws);      ws += up256((size_t)mb * R * 8);
     uint64_t* sorted = reinterpret_cast<uint64_t*>(ws);     ws += up256((size_t)mb * R * 8);
     const size_t temp_bytes = build_sort_temp_bytes(mb * R);
@@ -349,6 +350,8 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
         if (done + bs > n) bs = n - done;
         sp.qcodes = codes + done * (int64_t)code_row_words(nw, encoding);
         sp.nq = bs;
+        sp.order = launch_query_order(sp, order, stream, &e) ? order : nullptr;   // long searches first (large batches only)
+        if (e != hipSuccess) return e;
         e = launch_beam_search(sp, 0, stream);
         if (e != hipSuccess) return e;
         bp.done = done; bp.bs = bs;
