@@ -251,6 +251,20 @@ def test_search_wide_beams(qv, ef):
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
+@pytest.mark.parametrize("nq", [4095, 4096, 4097, 4608, 5000])
+def test_search_batches_around_the_launch_order_threshold(qv, nq):
+    # from 4,096 queries on, workgroups pick their queries through a launch order (ranked per 512-query slice and
+    # interleaved; the last slice may be ragged): every query must still be searched exactly once
+    rng = np.random.default_rng(nq)
+    n, d = 4000, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    q[::97] = q[0]                               # equal queries: equal distances to the entry node
+    adj = datagen.random_regular_graph(n, 12, seed=3)
+    ref, out = _run_both(qv, x, q, adj, entry=17, k=5, ef=24, visit_cap=64)
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
 def test_search_degenerate_graphs(qv):
     rng = np.random.default_rng(3)
     n, d = 500, 96
