@@ -143,7 +143,7 @@ int qv_timer_read(qv_timer* t, float* ms, int max_calls);
 
 /*
  * Brute-force scan in code space and overlap probe (paper Sec. 6, "Practical compatibility test": compare
- * the code-ranked top K with the float32-ranked top K on a sample before building an index; Sec. 5.4,
+ * the code-ranked top K with the float32-ranked top K on a sample before building an index; Sec. 5.5,
  * Table 10 reports the same "Top-10 overlap").
  *    qv_bq_scan: for every query code the K base codes with the smallest (distance, id).
  *       codes   device, [n][qv_code_words(d)];  qcodes device, [nq][qv_code_words(d)] (qv_encode's layout)
@@ -179,7 +179,7 @@ int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double
                    int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The two alternative encodings of the paper's ablation (Sec. 5.4 "Encoding Ablation", Table 10), through the
+ * The two alternative encodings of the paper's ablation (Sec. 5.5 "Encoding Ablation", Table 10), through the
  * same path.  Every *_enc call is its namesake above with an `encoding` argument; QV_ENC_SM is the method itself.
  *    QV_ENC_SIGN1  "1-bit sign": the sign plane alone, qv_code_words_enc(d) = ceil(d/64) words per vector;
  *                  distance = number of differing signs.

@@ -21,7 +21,7 @@ _SRC = os.path.join(_HERE, "quiver_oracle.c")
 _LIB = os.path.join(_HERE, "libquiver_oracle.so")
 
 EMPTY = 0xFFFFFFFF
-# encodings: Sign-Magnitude (the method), and the two of the paper's ablation (Sec. 5.4, Table 10)
+# encodings: Sign-Magnitude (the method), and the two of the paper's ablation (Sec. 5.5, Table 10)
 SM, SIGN1, SQ2 = 0, 1, 2
 
 

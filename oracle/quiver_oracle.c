@@ -34,7 +34,7 @@
  *     rounded to float once, ordered by (score descending, id ascending).
  *
  *
- * The two alternative encodings of the paper's ablation (Sec. 5.4 "Encoding
+ * The two alternative encodings of the paper's ablation (Sec. 5.5 "Encoding
  * Ablation", Table 10) are here as well, selected by an `enc` argument of the
  * *_enc entry points (0 = Sign-Magnitude, the default everywhere else):
  *   - enc 1, "1-bit sign": pos_i only, distance = number of differing signs.
@@ -202,7 +202,7 @@ int orc_sm_distance_pairs(const uint64_t *codes_a, const int64_t *ia, const uint
 }
 
 /* ------------------------------------------------------------------ */
-/* Ablation encodings (Sec. 5.4, Table 10).                            */
+/* Ablation encodings (Sec. 5.5, Table 10).                            */
 /* ------------------------------------------------------------------ */
 #define ORC_ENC_SM 0
 #define ORC_ENC_SIGN1 1
@@ -511,7 +511,7 @@ int orc_search(const float *queries, int64_t nq, int64_t n, int d, int R, const 
 
 /* ------------------------------------------------------------------ */
 /* Brute-force scan in code space (Sec. 6 "Practical compatibility     */
-/* test"; Sec. 5.4 Table 10 "Top-10 overlap"): for every query code    */
+/* test"; Sec. 5.5 Table 10 "Top-10 overlap"): for every query code    */
 /* the K base codes with the smallest (distance, id), by computing     */
 /* every distance.  ids/dist: [nq][K], ORC_EMPTY padded when n < K.    */
 /* ------------------------------------------------------------------ */

@@ -213,7 +213,7 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel(const float* __r
     exact_magnitude_plane(xv, d, W, cv, acc[wv], digits[wv], lane);
 }
 
-// ---- the two encodings of the paper's ablation (Sec. 5.4 "Encoding Ablation", Table 10) ----------------
+// ---- the two encodings of the paper's ablation (Sec. 5.5 "Encoding Ablation", Table 10) ----------------
 // 1-bit sign: the sign plane alone.  One wave per vector, 64 dimensions per ballot.
 __global__ __launch_bounds__(64 * ENC_WAVES) void encode_sign1_kernel(const float* __restrict__ x, int64_t n, int d,
                                                                       uint64_t* __restrict__ codes,

@@ -1,4 +1,4 @@
-// Brute-force scan in code space (paper Sec. 6, "Practical compatibility test"; Sec. 5.4, Table 10
+// Brute-force scan in code space (paper Sec. 6, "Practical compatibility test"; Sec. 5.5, Table 10
 // "Top-10 overlap"): for every query code, the K base codes with the smallest (distance, id).
 //
 // All-pairs distances are arithmetic-bound, not bandwidth-bound: a base code is reused by every query.

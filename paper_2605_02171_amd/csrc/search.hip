@@ -63,7 +63,7 @@ __device__ __forceinline__ void sm_accumulate(uint64_t pv, uint64_t sv, uint64_t
 }
 
 // The same step for any of the three encodings (ENC_SM: the method; ENC_SIGN1, ENC_SQ2: the two of the
-// paper's ablation, Sec. 5.4 / Table 10).  w0, w1: the node's first and second bit-plane word; q0, q1,
+// paper's ablation, Sec. 5.5 / Table 10).  w0, w1: the node's first and second bit-plane word; q0, q1,
 // q2: the query's words as code_query_words() prepared them.
 //   ENC_SIGN1  distance = pc(sign_v xor sign_q)                                  (w1, q1, q2 unused)
 //   ENC_SQ2    level = 2*hi + lo; |level_v - level_q| = sum over k = 1..3 of [level_v >= k] xor [level_q >= k];

@@ -1,4 +1,4 @@
-"""GPU parity for the two ablation encodings (paper Sec. 5.4, Table 10): 1-bit sign with Hamming distance and the
+"""GPU parity for the two ablation encodings (paper Sec. 5.5, Table 10): 1-bit sign with Hamming distance and the
 2-bit uniform quantiser with L1 distance, through encode, distance, scan, beam search and graph construction."""
 import numpy as np
 import pytest

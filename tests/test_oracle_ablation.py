@@ -1,4 +1,4 @@
-"""Pins for the oracle's two ablation encodings (paper Sec. 5.4 "Encoding Ablation", Table 10):
+"""Pins for the oracle's two ablation encodings (paper Sec. 5.5 "Encoding Ablation", Table 10):
 1-bit sign with Hamming distance and a 2-bit uniform quantiser with L1 distance.
 
 The paper prints no worked example for them, so the pins are hand-worked vectors, reductions to the
