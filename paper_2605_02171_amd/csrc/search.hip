@@ -4,10 +4,12 @@
 // Mapping to gfx950: one 64-lane wavefront per query, one wavefront per workgroup.
 //   * candidate list ("pool"): ef sorted 64-bit keys held in registers, entry e in lane e%64,
 //     register e/64.  key = dist << 33 | id << 1 | expanded, so integer order is (dist, id) order.
-//   * visited set: exact bucketed hash table of ids in LDS (one 16-byte bucket per probe, LDS
-//     compare-and-swap to claim a slot).  When it is nearly full it stops taking new ids; from
-//     then on a node may be evaluated twice, which cannot change the list (see merge_new_keys)
-//     and is reported in the status word.
+//   * visited set: bucketed table of ids in LDS (one 16-byte bucket per probe, LDS compare-and-swap to
+//     claim a slot; 16-bit tags that identify an id exactly, or 32-bit ids).  By default it is a small
+//     cache in which new ids displace old ones, so that 16 queries fit a compute unit; a forgotten
+//     node that comes up again is evaluated again, which cannot change the list (see merge_new_keys)
+//     and is reported in the status word.  The other mode never forgets and stops taking ids when
+//     nearly full.
 //   * expansion: lane j reads adj[u][j] (one coalesced row; the row of the runner-up is loaded one
 //     expansion ahead), lanes filter their ids through the visited table, survivors are compacted
 //     into LDS, then G lanes cooperate on one neighbour's code: lane s of a group loads words s,
@@ -20,6 +22,8 @@
 //     the ef smallest keys of (old pool U new keys); that set does not depend on the order in
 //     which neighbours are considered, so expanding all neighbours at once reproduces the
 //     sequential algorithm exactly.
+//   * launch order: workgroup b runs query order[b]; batches of 4,096 queries and more start their
+//     probably-longest queries first (query_order_kernel).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
