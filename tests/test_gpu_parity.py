@@ -351,3 +351,36 @@ def test_search_with_cold_vectors_in_pinned_host_memory(qv):
     out = qv.search(index, torch.from_numpy(q).cuda(), 10, 64, trace=True, visit_cap=256)
     torch.cuda.synchronize()
     _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+def test_search_replays_from_a_captured_graph(qv):
+    # qv_search allocates nothing and records only kernels: with caller-owned workspace and outputs the whole call
+    # can be captured once and replayed on new query contents; every replay must equal an eager call
+    w = datagen.scaled("C3", n=20_000, nq=4500)          # above the launch-order threshold
+    x = datagen.make_base(w)
+    adj, entry = graph.build_graph(x, 32, 32, 1.2)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, entry)
+    k, ef = 10, 48
+    rng = np.random.default_rng(5)
+    static_q = torch.zeros((w.nq, w.d), dtype=torch.float32, device="cuda")
+    ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
+    i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device="cuda")
+    out = qv.SearchOutput(i32(w.nq, k), torch.zeros((w.nq, k), dtype=torch.float32, device="cuda"),
+                          cand_ids=i32(w.nq, ef), cand_dist=i32(w.nq, ef), n_cand=i32(w.nq), n_expanded=i32(w.nq),
+                          n_dist_evals=i32(w.nq), status=i32(w.nq))
+    qv.search(index, static_q, k, ef, workspace=ws, out=out)             # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        qv.search(index, static_q, k, ef, workspace=ws, out=out)
+    for rep in range(3):
+        q = torch.from_numpy(rng.standard_normal((w.nq, w.d)).astype(np.float32)).cuda()
+        eager = qv.search(index, q, k, ef, trace=True)                   # the program's own eager work between replays
+        torch.cuda.synchronize()
+        static_q.copy_(q)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.cand_ids, eager.cand_ids) and torch.equal(out.cand_dist, eager.cand_dist), rep
+        assert torch.equal(out.ids, eager.ids) and torch.equal(out.scores, eager.scores), rep
+        assert torch.equal(out.n_expanded, eager.n_expanded), rep
