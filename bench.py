@@ -78,8 +78,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=10000, help="queries the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (queries would be sharded over replicas of the index; "
-              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (on several, the queries would be sharded over replicas "
+              "of the index). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import torch

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def note(msg: str) -> None:
-    """Progress line that survives pytest's capture: appended to gpurun_out/test_progress.log."""
+    """Progress line that survives pytest's capture: appended to a log file in the run's output folder."""
     d = os.path.join(ROOT, "gpurun_out")
     try:
         os.makedirs(d, exist_ok=True)
