@@ -114,7 +114,7 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float*
 #pragma unroll
         for (int w = 0; w < W; ++w) {
             int i = (w << 6) + lane;
-            dst[w] = (v < n && i < d) ? xv[i] : 0.0f;
+            dst[w] = (v < n && i < d) ? __builtin_nontemporal_load(xv + i) : 0.0f;
         }
     };
     constexpr bool PIPELINED = W <= 16;  // longer rows are enough bytes in flight by themselves
