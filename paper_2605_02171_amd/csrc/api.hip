@@ -248,7 +248,10 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     // ef = 64).  QV_VISITED_EXACT: about two slots per expected distance evaluation (~45 per unit of ef at
     // degree 64), as far as 64 KB of LDS per query allow.
     const bool cache = index->visited_mode != QV_VISITED_EXACT;
-    int slots = index->visited_slots > 0 ? index->visited_slots : (cache ? 4096 : 96 * ef + 2048);
+    // (wider beams: the merge area grows to 8.7 KB at ef = 1024, so the cache shrinks to keep the queries per CU up;
+    // measured optima at 1M x 768: 3072 slots for ef 129..512, 1024 beyond)
+    const int cache_slots = ef <= 128 ? 4096 : (ef <= 512 ? 3072 : 1024);
+    int slots = index->visited_slots > 0 ? index->visited_slots : (cache ? cache_slots : 96 * ef + 2048);
     const size_t fixed = qv::beam_search_lds_bytes(sp.nw, 0, true, ef);
     const int max_narrow = (int)((65536 - fixed) / 2 / 1024 * 1024);
     if (slots > max_narrow) slots = max_narrow;
