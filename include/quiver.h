@@ -84,7 +84,7 @@ int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids
  * 2. Load (paper Sec. 4.2: hot data = codes + flat adjacency, cold data = float32 vectors).
  *    Creates a host-side handle that remembers the borrowed device buffers; copies nothing.
  *    adj    device, [n][R] uint32, QV_EMPTY = empty slot (rows need not be packed to the left)
- *    codes  device, [n][qv_code_words(d)] uint64 in qv_encode's layout
+ *    codes  device, [n][qv_code_words(d)] uint64 in qv_encode's layout (rows further apart: qv_index_set_code_stride)
  *    vecs   [n][d] float32, only read by the rerank: device memory, or host memory the device can address
  *           (hipHostMalloc / pinned): the paper's cold store then stays in host RAM and the rerank's ef rows per
  *           query travel over PCIe
@@ -221,6 +221,26 @@ int qv_index_set_encoding(qv_index* index, int encoding);
 #define QV_VISITED_EXACT 1
 #define QV_VISITED_CACHE 2
 int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode);
+
+/*
+ * Line-aligned code rows (a memory-layout option of this library, not of the paper; Sec. 4.2 fixes only what the hot
+ * data holds).  The search gathers code rows at random, and the memory system moves 128-byte lines: a 96-byte
+ * row (d = 384) stored densely straddles a line boundary every other time, a 240-byte row (d = 960) touches
+ * 2.75 lines on average instead of 2.  Rows stored `stride` words apart, stride * 8 a divisor or a multiple of
+ * 128, touch the fewest lines there are.
+ *   qv_code_stride_words  (host only) the stride, in 64-bit words, that minimises the lines per row for this d:
+ *                    the dense row length when padding gains nothing (d = 768: 192 bytes are two lines either
+ *                    way), else the row length rounded up to 16 / 32 / 64 bytes or to a multiple of 128 bytes.
+ *                    0 on invalid arguments.
+ *   qv_pad_codes     out[i*stride + w] = codes[i*words + w] for w < words = qv_code_words_enc(d, encoding),
+ *                    0 in the padding.  codes: device, dense rows; out: device, n * stride words, caller's;
+ *                    stride = words, or even and > words, at most 4 words + 16 (QV_ERR_INVALID_ARG otherwise).  Asynchronous on `stream`.
+ *   qv_index_set_code_stride  tells an index that the rows of its `codes` are `stride` words apart (default: dense).
+ *                    Only qv_search reads an index; every other entry point takes dense rows.
+ */
+int qv_code_stride_words(int d, int encoding);
+int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int stride, uint64_t* out, void* stream);
+int qv_index_set_code_stride(qv_index* index, int stride);
 
 const char* qv_strerror(int code);
 const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */

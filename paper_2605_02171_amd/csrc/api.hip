@@ -61,6 +61,7 @@ struct qv_index {
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
     int visited_mode;   // 0: choose from ef; QV_VISITED_EXACT; QV_VISITED_CACHE
     int encoding;       // QV_ENC_*: what `codes` holds and what the queries are encoded to
+    int code_stride;    // 64-bit words between rows of `codes`; 0: dense
     qv_timer* timer;
 };
 
@@ -182,7 +183,7 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->encoding = QV_ENC_SM; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->encoding = QV_ENC_SM; ix->code_stride = 0; ix->timer = nullptr;
     *out = ix;
     return QV_OK;
 }
@@ -206,6 +207,37 @@ int qv_index_set_encoding(qv_index* index, int encoding) {
     if (!index) return QV_ERR_NULL;
     if (!enc_ok(encoding)) return QV_ERR_INVALID_ARG;
     index->encoding = encoding;
+    return QV_OK;
+}
+
+int qv_code_stride_words(int d, int encoding) {
+    const int words = qv_code_words_enc(d, encoding);
+    if (words == 0) return 0;
+    const int bytes = words * 8;
+    // smallest stride >= the row that divides 128 or is a multiple of it
+    int padded = bytes <= 16 ? 16 : (bytes <= 32 ? 32 : (bytes <= 64 ? 64 : (bytes + 127) / 128 * 128));
+    // lines a row touches on average: dense rows start at every multiple of gcd(bytes, 128) within a line
+    int g = bytes, r = 128;
+    while (r) { int t = g % r; g = r; r = t; }
+    const double dense_lines = (bytes + 128 - g) / 128.0, padded_lines = padded <= 128 ? 1.0 : padded / 128.0;
+    return padded_lines < dense_lines ? padded / 8 : words;
+}
+
+int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int stride, uint64_t* out, void* stream) {
+    const int words = qv_code_words_enc(d, encoding);
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (words == 0 || n < 0 || stride < words || (stride != words && (stride & 1)) || stride > 4 * words + 16) return QV_ERR_INVALID_ARG;
+    if (n == 0) return QV_OK;
+    if (!codes || !out) return QV_ERR_NULL;
+    hipError_t e = qv::launch_pad_codes(codes, n, words, stride, out, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "code padding launch");
+}
+
+int qv_index_set_code_stride(qv_index* index, int stride) {
+    if (!index) return QV_ERR_NULL;
+    const int words = qv_code_words_enc(index->d, index->encoding);
+    if (stride != 0 && (stride < words || (stride != words && (stride & 1)) || stride > 4 * words + 16)) return QV_ERR_INVALID_ARG;
+    index->code_stride = stride;
     return QV_OK;
 }
 
@@ -241,6 +273,11 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
 
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes; sp.encoding = index->encoding;
+    sp.row_stride = qv::code_row_words((index->d + 63) / 64, index->encoding);
+    if (index->code_stride > 0) {
+        if (index->code_stride < sp.row_stride) return QV_ERR_INVALID_ARG;  // set before the encoding changed
+        sp.row_stride = index->code_stride;
+    }
     sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
     // Visited set.  Default: a cache of 4096 slots (8 KB of 16-bit tags): with the list and the merge area a
     // query then needs about 10 KB of LDS, so 16 queries fit a compute unit and registers, not LDS, bound the

@@ -335,7 +335,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     SearchParams sp{};
-    sp.adj = adj; sp.codes = codes; sp.encoding = encoding; sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
+    sp.adj = adj; sp.codes = codes; sp.encoding = encoding; sp.row_stride = code_row_words(nw, encoding); sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;
     sp.cand_ids = cand_ids; sp.cand_dist = cand_dist; sp.n_cand = n_cand;
     sp.n_expanded = nullptr; sp.n_evals = nullptr; sp.status = nullptr; sp.visit_order = nullptr; sp.visit_cap = 0;
     sp.order = nullptr;

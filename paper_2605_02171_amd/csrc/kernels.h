@@ -16,9 +16,10 @@ constexpr uint32_t QV_STATUS_BAD_EDGE_BIT = 4u;
 
 struct SearchParams {
     const uint32_t* adj;     // [n][R]
-    const uint64_t* codes;   // [n][code_row_words(nw, encoding)]
+    const uint64_t* codes;   // [n] rows of code_row_words(nw, encoding) words, row_stride words apart
     const uint64_t* qcodes;  // [nq][code_row_words(nw, encoding)]
     int encoding;            // ENC_*
+    int row_stride;          // 64-bit words between the rows of `codes` (even, >= the row's words); qcodes are dense
     int64_t n;
     int64_t nq;
     int nw;                  // 64-bit words per bit-plane
@@ -57,6 +58,7 @@ struct RerankParams {
 
 hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status,
                          hipStream_t stream);
+hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int words, int stride, uint64_t* out, hipStream_t stream);
 hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
                               int64_t npairs, int d, int encoding, uint32_t* out, hipStream_t stream);
 hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,

@@ -447,7 +447,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             for (int b = 0; b < G; ++b) {
                 const int ri = b * RPP + grp;
                 if (ri < m) {
-                    const uint64_t* row = p.codes + (int64_t)list[ri] * (PLANES * NW_T);
+                    const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
                     if constexpr (BLOCKED) {
                         const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
                         const uint4* m4 = reinterpret_cast<const uint4*>(row + NW_T + sub * KW);
@@ -516,7 +516,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     for (int b = 0; b < BATCH; ++b) {
                         int ri = base + b * RPP + grp;
                         if (ri < m) {
-                            const uint64_t* row = p.codes + (int64_t)list[ri] * (PLANES * NW_T);
+                            const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
 #pragma unroll
                             for (int i = 0; i < KW; ++i) {
                                 int w = sub + i * G;
@@ -549,7 +549,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     int ri = base + grp;
                     uint32_t c1 = 0, c2 = 0, c3 = 0;
                     if (ri < m) {
-                        const uint64_t* row = p.codes + (int64_t)list[ri] * RW;
+                        const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
                         for (int w = sub; w < NW; w += G) {
                             code_accumulate<ENC>(row[w], PLANES == 2 ? row[NW + w] : 0ull, qlds[w], qlds[NW + w],
                                                  qlds[2 * NW + w], c1, c2, c3);
@@ -752,7 +752,7 @@ constexpr int ORDER_BLOCK = 512;
 
 __global__ __launch_bounds__(ORDER_BLOCK) void query_order_kernel(const uint64_t* __restrict__ qcodes,
                                                                   const uint64_t* __restrict__ codes, int64_t nq, int nw,
-                                                                  int encoding, uint32_t entry,
+                                                                  int encoding, uint32_t entry, int row_stride,
                                                                   uint32_t* __restrict__ order) {
     __shared__ uint32_t keys[ORDER_BLOCK];
     const int tid = threadIdx.x;
@@ -760,7 +760,7 @@ __global__ __launch_bounds__(ORDER_BLOCK) void query_order_kernel(const uint64_t
     uint32_t key = (uint32_t)(ORDER_BLOCK - 1 - tid);           // beyond the batch: below every real key
     if (q < nq) {
         const int rw = code_row_words_dev(nw, encoding);
-        const uint64_t* ce = codes + (int64_t)entry * rw;
+        const uint64_t* ce = codes + (int64_t)entry * row_stride;
         const uint64_t* cq = qcodes + q * rw;
         uint32_t c1 = 0, c2 = 0, c3 = 0;
         for (int w = 0; w < nw; ++w) {
@@ -795,7 +795,7 @@ bool launch_query_order(const SearchParams& p, uint32_t* order, hipStream_t stre
     // fewer queries than resident waves all start at once; very large batches amortise their tail
     if (p.nq < 4096 || p.nq > (1 << 20)) return false;
     hipLaunchKernelGGL(query_order_kernel, dim3((unsigned)((p.nq + ORDER_BLOCK - 1) / ORDER_BLOCK)), dim3(ORDER_BLOCK), 0,
-                       stream, p.qcodes, p.codes, p.nq, p.nw, p.encoding, p.entry, order);
+                       stream, p.qcodes, p.codes, p.nq, p.nw, p.encoding, p.entry, p.row_stride, order);
     *err = hipGetLastError();
     return *err == hipSuccess;
 }

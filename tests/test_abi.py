@@ -51,6 +51,41 @@ def test_sizes(lib):
     assert f(10, 768, 65, 64) == 0 and f(10, 0, 1, 8) == 0 and f(10, 768, 1, 2000) == 0 and f(-1, 8, 1, 8) == 0
 
 
+def test_line_aligned_row_strides(lib):
+    """The recommended stride is the dense row unless padding lowers the mean number of 128-byte lines a row
+    touches; check that against a brute-force count over every row offset."""
+    f = lib.qv_code_stride_words
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_int, ctypes.c_int]
+    g = lib.qv_code_words_enc
+    g.restype = ctypes.c_int
+    g.argtypes = [ctypes.c_int, ctypes.c_int]
+
+    def mean_lines(row_bytes, stride_bytes):
+        total = 0
+        for i in range(128):                      # offsets repeat after at most 128 rows
+            a = i * stride_bytes
+            total += (a + row_bytes - 1) // 128 - a // 128 + 1
+        return total / 128
+
+    assert [f(d, 0) for d in (64, 128, 192, 384, 512, 768, 960, 1024, 3072)] == [2, 4, 8, 16, 16, 24, 32, 32, 96]
+    assert [f(d, 1) for d in (64, 192, 384, 768, 960)] == [1, 4, 8, 16, 16]
+    assert f(0, 0) == 0 and f(768, 9) == 0 and f(70000, 0) == 0
+    for enc in (0, 1, 2):
+        for d in list(range(1, 2200, 37)) + [64, 384, 768, 960, 1024, 1536, 3072, 65536]:
+            words, stride = g(d, enc), f(d, enc)
+            assert stride >= words and (stride == words or stride % 2 == 0) and stride <= 4 * words + 16
+            dense, chosen = mean_lines(words * 8, words * 8), mean_lines(words * 8, stride * 8)
+            assert chosen <= dense
+            if stride != words:
+                assert chosen < dense                                      # padding only when it pays
+                assert chosen == max(1, -(-words * 8 // 128))             # and then a row touches the fewest lines possible
+            else:                                                          # no aligned stride would do better
+                bytes_ = words * 8
+                aligned = next(s for s in (16, 32, 64) if s >= bytes_) if bytes_ <= 64 else -(-bytes_ // 128) * 128
+                assert mean_lines(bytes_, aligned) >= dense
+
+
 def test_host_side_argument_errors(lib):
     P = ctypes.c_void_p
     fake = P(0x1000)  # never dereferenced: every call below fails before any launch
@@ -85,6 +120,19 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_index_set_tuning(h, 512, 0, 0, 0) == -1 and lib.qv_index_set_tuning(h, 0, 3, 0, 0) == -1
     assert lib.qv_index_set_tuning(h, 0, 0, 16, 0) == -1 and lib.qv_index_set_tuning(h, 8192, 4, 32, 0) == 0
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 3) == -1 and lib.qv_index_set_tuning(h, 4096, 2, 0, 2) == 0
+    # row stride of the index's codes: the dense length, or even and longer (d = 8: one word per plane, 2 per row)
+    lib.qv_index_set_code_stride.argtypes = [P, ctypes.c_int]
+    assert lib.qv_index_set_code_stride(h, 0) == 0 and lib.qv_index_set_code_stride(h, 2) == 0
+    assert lib.qv_index_set_code_stride(h, 4) == 0 and lib.qv_index_set_code_stride(h, 16) == 0
+    assert lib.qv_index_set_code_stride(h, 1) == -1 and lib.qv_index_set_code_stride(h, 3) == -1
+    assert lib.qv_index_set_code_stride(h, 4096) == -1 and lib.qv_index_set_code_stride(None, 2) == -2
+    lib.qv_pad_codes.argtypes = [P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P]
+    assert lib.qv_pad_codes(fake, 5, 384, 0, 11, fake, None) == -1       # shorter than the row
+    assert lib.qv_pad_codes(fake, 5, 384, 0, 13, fake, None) == -1       # odd
+    assert lib.qv_pad_codes(fake, 5, 384, 7, 16, fake, None) == -1       # unknown encoding
+    assert lib.qv_pad_codes(fake, 5, 0, 0, 16, fake, None) == -3
+    assert lib.qv_pad_codes(None, 5, 384, 0, 16, fake, None) == -2
+    assert lib.qv_pad_codes(None, 0, 384, 0, 16, None, None) == 0        # nothing to do
     lib.qv_index_free.argtypes = [P]
     lib.qv_index_free(h)
     lib.qv_index_free(None)

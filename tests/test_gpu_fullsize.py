@@ -42,7 +42,7 @@ def _exact_topk(xd, qd, k, metric):
     return best_i.cpu().numpy()
 
 
-def _full_case(qv, name, efs, n_sample, L=None, R=None):
+def _full_case(qv, name, efs, n_sample, L=None, R=None, aligned_rows=False):
     w = datagen.WORKLOADS[name]
     t0 = time.time()
     util.note(f"{name}: generating {w.n} x {w.d}")
@@ -112,6 +112,20 @@ def _full_case(qv, name, efs, n_sample, L=None, R=None):
         qc = oracle.encode(q[qi])
         want = oracle.sm_distance_pairs(qc, np.arange(200), codes, cid[qi, ci].astype(np.int64), w.d)
         assert (want == cds[qi, ci]).all()
+    if aligned_rows:
+        # the same batch through code rows padded to whole 128-byte lines: the sample against the oracle again,
+        # the rest of the batch against the properties above by way of the dense run's lists
+        ef = efs[-1]
+        util.note(f"{name}: ef={ef} with line-aligned code rows (stride {qv.code_stride_words(w.d)} words)")
+        index2 = qv.Index(qv.from_numpy_u32(adj), qv.pad_codes(gcodes, w.d), xd, entry)
+        out2 = qv.search(index2, qd, w.k, ef, trace=True, visit_cap=256)
+        torch.cuda.synchronize()
+        cid2, cds2 = qv.to_numpy_u32(out2.cand_ids), qv.to_numpy_u32(out2.cand_dist)
+        assert (cid2[:n_sample] == ref.cand_ids).all() and (cds2[:n_sample] == ref.cand_dist).all()
+        assert (qv.to_numpy_u32(out2.visit_order)[:n_sample] == ref.visit_order).all()
+        util.assert_topk_matches(qv.to_numpy_u32(out2.ids)[:n_sample], out2.scores.cpu().numpy()[:n_sample], ref.ids, ref.scores)
+        assert (cid2 == cid).all() and (cds2 == cds).all()
+        del index2
     del index, xd, gcodes
     torch.cuda.empty_cache()
 
@@ -121,7 +135,7 @@ def test_full_size_768d_headline_all_ef(qv):
 
 
 def test_full_size_384d(qv):
-    _full_case(qv, "C3", efs=(64,), n_sample=1000, L=64)
+    _full_case(qv, "C3", efs=(64,), n_sample=1000, L=64, aligned_rows=True)
 
 
 def test_full_size_512d_structureless(qv):

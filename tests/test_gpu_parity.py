@@ -265,6 +265,35 @@ def test_search_batches_around_the_launch_order_threshold(qv, nq):
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
+@pytest.mark.parametrize("d,stride,enc,nq", [(384, None, 0, 37), (960, None, 0, 37), (100, 6, 0, 37), (768, 32, 0, 37),
+                                             (192, None, 1, 37), (384, None, 2, 37), (384, None, 0, 4200)])
+def test_search_with_line_aligned_code_rows(qv, d, stride, enc, nq):
+    """Code rows stored further apart than their length (padding zeroed): the padded copy is the dense
+    one row by row, and the search through it returns what the oracle returns on dense rows."""
+    rng = np.random.default_rng(d + 7 * enc)
+    n, R, ef, k = 3000, 32, 48, 10
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    adj = datagen.random_regular_graph(n, R, seed=d, fill=0.9)
+    codes = oracle.encode(x, threads=8, enc=enc)
+    ref = oracle.search(q, adj, codes, x, 11, k, ef, visit_cap=200, threads=8, enc=enc)
+    xd = torch.from_numpy(x).cuda()
+    words = qv.code_words(d, enc)
+    if stride is None:
+        stride = qv.code_stride_words(d, enc)
+        assert stride > words                       # these widths are the ones padding helps
+    padded = qv.pad_codes(qv.encode(xd, enc=enc), d, stride, enc=enc)
+    got = qv.to_numpy_u64(padded)
+    assert got.shape == (n, stride) and (got[:, :words] == codes).all() and (got[:, words:] == 0).all()
+    index = qv.Index(qv.from_numpy_u32(adj), padded, xd, 11, enc=enc)
+    qd = torch.from_numpy(q).cuda()
+    for mode in (qv.VISITED_CACHE, qv.VISITED_EXACT):
+        index.set_tuning(0, 0, 0, mode)
+        out = qv.search(index, qd, k, ef, trace=True, visit_cap=200)
+        torch.cuda.synchronize()
+        _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
 def test_search_degenerate_graphs(qv):
     rng = np.random.default_rng(3)
     n, d = 500, 96
