@@ -37,6 +37,10 @@ __device__ __forceinline__ bool split_abs(float x, uint32_t& m, int& sh) {
     return true;
 }
 
+// v_writelane_b32: `value` (wave-uniform) replaces lane `lane` of `old`; reached through the compiler's intrinsic so
+// that the compiler keeps the wait states between the compare that produced `value` and this instruction
+extern "C" __device__ int qv_writelane(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
 __device__ __forceinline__ bool is_positive(float x) { return (int32_t)__float_as_uint(x) > 0; }
 
 // float32 bounds around S/d: |x| > hi => D*|x| > S + margin;  |x| < lo => D*|x| < S - margin
@@ -96,7 +100,11 @@ __device__ __forceinline__ void exact_magnitude_plane(const float* __restrict__ 
 
 // Vectors of up to 64*W dimensions, W known at compile time: the whole vector sits in registers
 // (W values per lane), all loads are issued before the first use, the row is read exactly once and
-// the 2W code words leave through one coalesced store.
+// the 2W code words leave through one coalesced store.  The loop body has no branch but the rare exact
+// redo: rows beyond the end are clamped to the last row (loaded, never stored), the ragged tail of the
+// last word is clamped to the row's last element and zeroed, every per-dimension predicate is one
+// compare whose wave-wide result (a scalar register pair) is the plane's word, the "in doubt" test is
+// scalar arithmetic on those words, and the words are dropped into the lanes that store them.
 template <int W>
 __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float* __restrict__ x, int64_t n, int d,
                                                                     uint64_t* __restrict__ codes,
@@ -106,23 +114,28 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float*
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
     const int64_t stride = (int64_t)gridDim.x * ENC_WAVES;
+    const int tail_i = (W - 1) * 64 + lane;                   // this lane's dimension in the last word
+    const bool tail_valid = tail_i < d;
+    const int tail_off = tail_valid ? tail_i : d - 1;
+    const uint64_t tail_mask = __ballot(tail_valid);
+    // 1/d rounded to nearest: (S +- margin) * inv_d is within 2^-52 of the quotient, far inside the two
+    // float32 ulps by which the bounds are moved outwards
+    const double inv_d = 1.0 / (double)d;
+    const double margin_factor = (double)d * 0x1p-52;
     // grid-stride over vectors: the grid is sized to fill the chip a few times, not one wave per vector.
     // The next vector of this wave is loaded while the current one is processed, so a wave always has a
     // row of loads in flight.
     auto load_row = [&](int64_t v, auto& dst) {
-        const float* xv = x + v * (int64_t)d;
+        const float* xv = x + (v < n ? v : n - 1) * (int64_t)d;
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-            int i = (w << 6) + lane;
-            dst[w] = (v < n && i < d) ? __builtin_nontemporal_load(xv + i) : 0.0f;
-        }
+        for (int w = 0; w < W - 1; ++w) dst[w] = __builtin_nontemporal_load(xv + (w << 6) + lane);
+        dst[W - 1] = __builtin_nontemporal_load(xv + tail_off);
     };
     constexpr bool PIPELINED = W <= 16;  // longer rows are enough bytes in flight by themselves
     int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv;
     float xr[W], xnext[PIPELINED ? W : 1];
     if constexpr (PIPELINED) load_row(v, xnext);
     for (; v < n; v += stride) {
-        const float* xv = x + v * (int64_t)d;
         uint64_t* cv = codes + v * (int64_t)(2 * W);
         if constexpr (PIPELINED) {
 #pragma unroll
@@ -131,35 +144,43 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float*
         } else {
             load_row(v, xr);
         }
+        xr[W - 1] = tail_valid ? xr[W - 1] : 0.0f;
 
         double part = 0.0;
-        bool finite = true;
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-            finite &= (__float_as_uint(xr[w]) & 0x7F800000u) != 0x7F800000u;
-            part += (double)fabsf(xr[w]);
-        }
-        const double S = wave_sum(part);
-        const bool all_finite = __all(finite);
-        float lo, hi;
-        certain_bounds(S, d, lo, hi);
-        bool doubtful = false;
-        uint64_t mine = 0, mine2 = 0;  // lane l keeps code word l (and word 64 + l when 2W > 64)
+        for (int w = 0; w < W; ++w) part += (double)fabsf(xr[w]);
+        const double S = wave_sum(part);                       // the same bits in every lane
+        // finite magnitudes cannot overflow a double sum (d * 2^128 < 2^1024), so S tells whether all are
+        const bool all_finite = S < __builtin_huge_val();
+        const double margin = margin_factor * S;
+        const float h = (float)((S + margin) * inv_d), l = (float)((S - margin) * inv_d);
+        const float hi = __uint_as_float(__float_as_uint(h) + 2u);   // Inf + 2 is a NaN: then nothing is "certainly strong"
+        const uint32_t lb = __float_as_uint(l);
+        const float lo = __uint_as_float(lb >= 2u ? lb - 2u : 0u);
+
+        uint64_t doubt = 0;                                    // scalar: dimensions neither certainly strong nor certainly weak
+        int w0_lo = 0, w0_hi = 0, w1_lo = 0, w1_hi = 0;        // lane l keeps code word l (and word 64 + l when 2W > 64)
 #pragma unroll
         for (int w = 0; w < W; ++w) {
             const float a = fabsf(xr[w]);
-            const bool strong = a > hi;
-            doubtful |= ((w << 6) + lane < d) && !strong && !(a < lo);
+            const uint64_t sw = __ballot(a > hi);
+            const uint64_t ge = __ballot(a >= lo);
             const uint64_t pw = __ballot(is_positive(xr[w]));
-            const uint64_t sw = __ballot(strong);
-            if (lane == w) mine = pw;
-            if (W + w < 64) { if (lane == W + w) mine = sw; }
-            else { if (lane == W + w - 64) mine2 = sw; }
+            doubt |= (w == W - 1 ? ge & tail_mask : ge) & ~sw;
+            w0_lo = qv_writelane((int)(uint32_t)pw, w, w0_lo);
+            w0_hi = qv_writelane((int)(uint32_t)(pw >> 32), w, w0_hi);
+            if (W + w < 64) {
+                w0_lo = qv_writelane((int)(uint32_t)sw, W + w, w0_lo);
+                w0_hi = qv_writelane((int)(uint32_t)(sw >> 32), W + w, w0_hi);
+            } else {
+                w1_lo = qv_writelane((int)(uint32_t)sw, W + w - 64, w1_lo);
+                w1_hi = qv_writelane((int)(uint32_t)(sw >> 32), W + w - 64, w1_hi);
+            }
         }
-        if (lane < 2 * W && lane < 64) cv[lane] = mine;
-        if (2 * W > 64 && lane < 2 * W - 64) cv[64 + lane] = mine2;
+        if (lane < 2 * W && lane < 64) cv[lane] = ((uint64_t)(uint32_t)w0_hi << 32) | (uint32_t)w0_lo;
+        if (2 * W > 64 && lane < 2 * W - 64) cv[64 + lane] = ((uint64_t)(uint32_t)w1_hi << 32) | (uint32_t)w1_lo;
         if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
-        if (all_finite && __any(doubtful)) exact_magnitude_plane(xv, d, W, cv, acc[wv], digits[wv], lane);
+        if (all_finite && doubt != 0) exact_magnitude_plane(x + v * (int64_t)d, d, W, cv, acc[wv], digits[wv], lane);
     }
 }
 
