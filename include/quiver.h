@@ -59,6 +59,7 @@ int qv_code_words(int d);
  *           words of magnitude bits; dimension i is bit i%64 (bit 0 = LSB) of word i/64; bits
  *           of dimensions >= d are 0.
  *    status device, [n] uint32 or NULL: receives QV_STATUS_NONFINITE or 0 per vector.
+ *    0 <= n <= 2^32 (QV_ERR_INVALID_ARG otherwise; n = 0 does nothing).  Asynchronous on `stream`.
  */
 int qv_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* status, void* stream);
 

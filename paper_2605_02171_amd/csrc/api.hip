@@ -81,7 +81,7 @@ int qv_encode(const float* x, int64_t n, int d, uint64_t* codes, uint32_t* statu
 
 int qv_encode_enc(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status, void* stream) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (n < 0 || !enc_ok(encoding)) return QV_ERR_INVALID_ARG;
+    if (n < 0 || n > (1ll << 32) || !enc_ok(encoding)) return QV_ERR_INVALID_ARG;
     if (n == 0) return QV_OK;
     if (!x || !codes) return QV_ERR_NULL;
     hipError_t e = qv::launch_encode(x, n, d, encoding, codes, status, (hipStream_t)stream);

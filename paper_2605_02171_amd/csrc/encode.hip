@@ -100,20 +100,21 @@ __device__ __forceinline__ void exact_magnitude_plane(const float* __restrict__ 
 
 // Vectors of up to 64*W dimensions, W known at compile time: the whole vector sits in registers
 // (W values per lane), all loads are issued before the first use, the row is read exactly once and
-// the 2W code words leave through one coalesced store.  The loop body has no branch but the rare exact
-// redo: rows beyond the end are clamped to the last row (loaded, never stored), the ragged tail of the
-// last word is clamped to the row's last element and zeroed, every per-dimension predicate is one
-// compare whose wave-wide result (a scalar register pair) is the plane's word, the "in doubt" test is
-// scalar arithmetic on those words, and the words are dropped into the lanes that store them.
-template <int W>
+// the code words leave through one coalesced store.  The body has no branch but the rare exact redo:
+// the ragged tail of the last word is clamped to the row's last element and zeroed, every
+// per-dimension predicate is one compare whose wave-wide result (a scalar register pair) is the
+// plane's word, the "in doubt" test is scalar arithmetic on those words, and the words are dropped into
+// the lanes that store them.  A wave takes ROWS consecutive vectors (short rows: their independent
+// reductions overlap and their 2W ROWS <= 64 code words, contiguous in memory, still leave in one store).
+template <int W, int ROWS>
 __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float* __restrict__ x, int64_t n, int d,
                                                                     uint64_t* __restrict__ codes,
                                                                     uint32_t* __restrict__ status) {
+    static_assert(ROWS == 1 || 2 * W * ROWS <= 64, "the code words of a wave's vectors must fit one register");
     __shared__ unsigned long long acc[ENC_WAVES][EXACT_LIMBS];
     __shared__ uint32_t digits[ENC_WAVES][EXACT_LIMBS];
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
-    const int64_t stride = (int64_t)gridDim.x * ENC_WAVES;
     const int tail_i = (W - 1) * 64 + lane;                   // this lane's dimension in the last word
     const bool tail_valid = tail_i < d;
     const int tail_off = tail_valid ? tail_i : d - 1;
@@ -122,33 +123,29 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float*
     // float32 ulps by which the bounds are moved outwards
     const double inv_d = 1.0 / (double)d;
     const double margin_factor = (double)d * 0x1p-52;
-    // grid-stride over vectors: the grid is sized to fill the chip a few times, not one wave per vector.
-    // The next vector of this wave is loaded while the current one is processed, so a wave always has a
-    // row of loads in flight.
-    auto load_row = [&](int64_t v, auto& dst) {
-        const float* xv = x + (v < n ? v : n - 1) * (int64_t)d;
-#pragma unroll
-        for (int w = 0; w < W - 1; ++w) dst[w] = __builtin_nontemporal_load(xv + (w << 6) + lane);
-        dst[W - 1] = __builtin_nontemporal_load(xv + tail_off);
-    };
-    constexpr bool PIPELINED = W <= 16;  // longer rows are enough bytes in flight by themselves
-    int64_t v = (int64_t)blockIdx.x * ENC_WAVES + wv;
-    float xr[W], xnext[PIPELINED ? W : 1];
-    if constexpr (PIPELINED) load_row(v, xnext);
-    for (; v < n; v += stride) {
-        uint64_t* cv = codes + v * (int64_t)(2 * W);
-        if constexpr (PIPELINED) {
-#pragma unroll
-            for (int w = 0; w < W; ++w) xr[w] = xnext[w];
-            load_row(v + stride, xnext);
-        } else {
-            load_row(v, xr);
-        }
-        xr[W - 1] = tail_valid ? xr[W - 1] : 0.0f;
+    // No loop over vectors: with a body this short, many short-lived waves stream better than fewer waves
+    // that prefetch their next row (1M x 768: 0.53 against 0.58 ms).
+    const int64_t v0 = ((int64_t)blockIdx.x * ENC_WAVES + wv) * ROWS;
+    if (v0 >= n) return;  // whole wave leaves together; no block-wide barrier is used below
+    const int rows = n - v0 < ROWS ? (int)(n - v0) : ROWS;
 
+    float xr[ROWS][W];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const float* xv = x + (v0 + (r < rows ? r : rows - 1)) * (int64_t)d;   // beyond the end: the last row again
+#pragma unroll
+        for (int w = 0; w < W - 1; ++w) xr[r][w] = __builtin_nontemporal_load(xv + (w << 6) + lane);
+        xr[r][W - 1] = __builtin_nontemporal_load(xv + tail_off);
+    }
+
+    int w0_lo = 0, w0_hi = 0, w1_lo = 0, w1_hi = 0;   // lane l keeps code word l of the wave's vectors (and word 64 + l when 2W > 64)
+    uint32_t redo = 0, nonfinite = 0;                  // bit r: vector r needs the exact redo / holds Inf or NaN
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        xr[r][W - 1] = tail_valid ? xr[r][W - 1] : 0.0f;
         double part = 0.0;
 #pragma unroll
-        for (int w = 0; w < W; ++w) part += (double)fabsf(xr[w]);
+        for (int w = 0; w < W; ++w) part += (double)fabsf(xr[r][w]);
         const double S = wave_sum(part);                       // the same bits in every lane
         // finite magnitudes cannot overflow a double sum (d * 2^128 < 2^1024), so S tells whether all are
         const bool all_finite = S < __builtin_huge_val();
@@ -159,28 +156,35 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_kernel_reg(const float*
         const float lo = __uint_as_float(lb >= 2u ? lb - 2u : 0u);
 
         uint64_t doubt = 0;                                    // scalar: dimensions neither certainly strong nor certainly weak
-        int w0_lo = 0, w0_hi = 0, w1_lo = 0, w1_hi = 0;        // lane l keeps code word l (and word 64 + l when 2W > 64)
 #pragma unroll
         for (int w = 0; w < W; ++w) {
-            const float a = fabsf(xr[w]);
+            const float a = fabsf(xr[r][w]);
             const uint64_t sw = __ballot(a > hi);
             const uint64_t ge = __ballot(a >= lo);
-            const uint64_t pw = __ballot(is_positive(xr[w]));
+            const uint64_t pw = __ballot(is_positive(xr[r][w]));
             doubt |= (w == W - 1 ? ge & tail_mask : ge) & ~sw;
-            w0_lo = qv_writelane((int)(uint32_t)pw, w, w0_lo);
-            w0_hi = qv_writelane((int)(uint32_t)(pw >> 32), w, w0_hi);
-            if (W + w < 64) {
-                w0_lo = qv_writelane((int)(uint32_t)sw, W + w, w0_lo);
-                w0_hi = qv_writelane((int)(uint32_t)(sw >> 32), W + w, w0_hi);
+            const int at = r * 2 * W + w;
+            w0_lo = qv_writelane((int)(uint32_t)pw, at, w0_lo);
+            w0_hi = qv_writelane((int)(uint32_t)(pw >> 32), at, w0_hi);
+            if (at + W < 64) {
+                w0_lo = qv_writelane((int)(uint32_t)sw, at + W, w0_lo);
+                w0_hi = qv_writelane((int)(uint32_t)(sw >> 32), at + W, w0_hi);
             } else {
-                w1_lo = qv_writelane((int)(uint32_t)sw, W + w - 64, w1_lo);
-                w1_hi = qv_writelane((int)(uint32_t)(sw >> 32), W + w - 64, w1_hi);
+                w1_lo = qv_writelane((int)(uint32_t)sw, at + W - 64, w1_lo);
+                w1_hi = qv_writelane((int)(uint32_t)(sw >> 32), at + W - 64, w1_hi);
             }
         }
-        if (lane < 2 * W && lane < 64) cv[lane] = ((uint64_t)(uint32_t)w0_hi << 32) | (uint32_t)w0_lo;
-        if (2 * W > 64 && lane < 2 * W - 64) cv[64 + lane] = ((uint64_t)(uint32_t)w1_hi << 32) | (uint32_t)w1_lo;
-        if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
-        if (all_finite && doubt != 0) exact_magnitude_plane(x + v * (int64_t)d, d, W, cv, acc[wv], digits[wv], lane);
+        if (!all_finite) nonfinite |= 1u << r;
+        else if (doubt != 0) redo |= 1u << r;
+    }
+    uint64_t* cv = codes + v0 * (int64_t)(2 * W);
+    if (lane < 2 * W * rows && lane < 64) cv[lane] = ((uint64_t)(uint32_t)w0_hi << 32) | (uint32_t)w0_lo;
+    if (2 * W > 64 && lane < 2 * W - 64) cv[64 + lane] = ((uint64_t)(uint32_t)w1_hi << 32) | (uint32_t)w1_lo;
+    if (status && lane < rows) status[v0 + lane] = (nonfinite >> lane) & 1u ? QV_STATUS_NONFINITE_BIT : 0u;
+    if (redo != 0) {
+        for (int r = 0; r < rows; ++r)
+            if ((redo >> r) & 1u)
+                exact_magnitude_plane(x + (v0 + r) * (int64_t)d, d, W, cv + r * 2 * W, acc[wv], digits[wv], lane);
     }
 }
 
@@ -387,7 +391,8 @@ hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids
 hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status,
                          hipStream_t stream) {
     if (n == 0) return hipSuccess;
-    dim3 grid((unsigned)((n + ENC_WAVES - 1) / ENC_WAVES)), block(64 * ENC_WAVES);
+    dim3 grid((unsigned)((n + ENC_WAVES - 1) / ENC_WAVES)), block(64 * ENC_WAVES);   // one vector per wave; n <= 2^32 (checked by the caller)
+    auto grid_for = [&](int rows) { return dim3((unsigned)((n + ENC_WAVES * rows - 1) / (ENC_WAVES * rows))); };
     if (encoding == ENC_SIGN1) {
         hipLaunchKernelGGL(encode_sign1_kernel, grid, block, 0, stream, x, n, d, codes, status);
         return hipGetLastError();
@@ -396,12 +401,12 @@ hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_
         hipLaunchKernelGGL(encode_sq2_kernel, grid, block, 0, stream, x, n, d, codes, status);
         return hipGetLastError();
     }
-    const unsigned full = 256 * 8 * 4;  // 4 rounds of 8 workgroups per CU
-    dim3 pgrid(grid.x < full ? grid.x : full);
+    // vectors per wave, measured at 1M vectors: 64 x W dimensions of 4 (256-d: 0.168 against 0.191 ms with one) and
+    // 6 words (384-d with two: 0.263 against 0.300 ms) gain; from 8 words on one vector per wave is as fast
     switch ((d + 63) / 64) {
-#define QV_ENC_CASE(W) case W: hipLaunchKernelGGL(encode_kernel_reg<W>, pgrid, block, 0, stream, x, n, d, codes, status); break;
-        QV_ENC_CASE(1) QV_ENC_CASE(2) QV_ENC_CASE(4) QV_ENC_CASE(6) QV_ENC_CASE(8) QV_ENC_CASE(12)
-        QV_ENC_CASE(16) QV_ENC_CASE(24) QV_ENC_CASE(32) QV_ENC_CASE(48)
+#define QV_ENC_CASE(W, ROWS) case W: hipLaunchKernelGGL((encode_kernel_reg<W, ROWS>), grid_for(ROWS), block, 0, stream, x, n, d, codes, status); break;
+        QV_ENC_CASE(1, 8) QV_ENC_CASE(2, 4) QV_ENC_CASE(4, 4) QV_ENC_CASE(6, 2) QV_ENC_CASE(8, 1) QV_ENC_CASE(12, 1)
+        QV_ENC_CASE(16, 1) QV_ENC_CASE(24, 1) QV_ENC_CASE(32, 1) QV_ENC_CASE(48, 1)
 #undef QV_ENC_CASE
         default: hipLaunchKernelGGL(encode_kernel, grid, block, 0, stream, x, n, d, codes, status);
     }

@@ -94,6 +94,7 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_encode(fake, 4, 70000, fake, None, None) == -3
     assert lib.qv_encode(None, 4, 8, fake, None, None) == -2
     assert lib.qv_encode(fake, -1, 8, fake, None, None) == -1
+    assert lib.qv_encode(fake, (1 << 32) + 1, 8, fake, None, None) == -1
     assert lib.qv_encode(None, 0, 8, None, None, None) == 0          # empty input is fine
     lib.qv_bq_distance.argtypes = [P, P, P, P, ctypes.c_int64, ctypes.c_int, P, P]
     assert lib.qv_bq_distance(fake, fake, fake, None, 3, 8, fake, None) == -2

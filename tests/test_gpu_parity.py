@@ -72,6 +72,26 @@ def test_encode_flags_non_finite_and_empty_input(qv):
     assert empty.shape == (0, 4)
 
 
+@pytest.mark.parametrize("d", [40, 64, 100, 128, 250, 256, 384])
+def test_encode_short_rows_share_a_wave(qv, d):
+    """Widths at which one wave encodes several consecutive vectors: every count of leftover vectors, with
+    vectors that need the exact redo (equal magnitudes) and non-finite ones anywhere among them."""
+    rng = np.random.default_rng(d)
+    for n in (1, 2, 3, 5, 7, 8, 9, 31, 33, 67):
+        x = rng.standard_normal((n, d)).astype(np.float32)
+        equal = rng.random(n) < 0.3
+        x[equal] = np.float32(0.37) * rng.choice([-1.0, 1.0], size=(int(equal.sum()), d)).astype(np.float32)
+        bad = (rng.random(n) < 0.2) & ~equal
+        for i in np.flatnonzero(bad):
+            x[i, rng.integers(0, d)] = [np.inf, -np.inf, np.nan][i % 3]
+        codes, status = qv.encode(torch.from_numpy(x).cuda(), want_status=True)
+        assert (qv.to_numpy_u32(status) == bad.astype(np.uint32)).all()
+        if (~bad).any():
+            want = oracle.encode(x[~bad], threads=2)
+            assert (qv.to_numpy_u64(codes)[~bad] == want).all(), (d, n)
+            assert (want[equal[~bad]][:, want.shape[1] // 2:] == 0).all()      # equal magnitudes: nothing is strong
+
+
 @pytest.mark.parametrize("d", [1, 64, 100, 768, 3072])
 def test_bq_distance_bit_exact(qv, d):
     rng = np.random.default_rng(7 + d)
