@@ -405,8 +405,9 @@ hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_
     // 6 words (384-d with two: 0.263 against 0.300 ms) gain; from 8 words on one vector per wave is as fast
     switch ((d + 63) / 64) {
 #define QV_ENC_CASE(W, ROWS) case W: hipLaunchKernelGGL((encode_kernel_reg<W, ROWS>), grid_for(ROWS), block, 0, stream, x, n, d, codes, status); break;
-        QV_ENC_CASE(1, 8) QV_ENC_CASE(2, 4) QV_ENC_CASE(4, 4) QV_ENC_CASE(6, 2) QV_ENC_CASE(8, 1) QV_ENC_CASE(12, 1)
-        QV_ENC_CASE(16, 1) QV_ENC_CASE(24, 1) QV_ENC_CASE(32, 1) QV_ENC_CASE(48, 1)
+        QV_ENC_CASE(1, 8) QV_ENC_CASE(2, 4) QV_ENC_CASE(3, 4) QV_ENC_CASE(4, 4) QV_ENC_CASE(5, 2) QV_ENC_CASE(6, 2)
+        QV_ENC_CASE(8, 1) QV_ENC_CASE(10, 1) QV_ENC_CASE(12, 1) QV_ENC_CASE(15, 1) QV_ENC_CASE(16, 1) QV_ENC_CASE(20, 1)
+        QV_ENC_CASE(24, 1) QV_ENC_CASE(32, 1) QV_ENC_CASE(48, 1) QV_ENC_CASE(64, 1)
 #undef QV_ENC_CASE
         default: hipLaunchKernelGGL(encode_kernel, grid, block, 0, stream, x, n, d, codes, status);
     }
