@@ -1,15 +1,15 @@
 // 2-bit Sign-Magnitude encoder (paper Sec. 3.1, the two encoding equations) for gfx950.
 //
-// One wavefront encodes one vector.  Lane l of the wave owns dimensions l, l+64, l+128, ...,
-// so every load instruction reads 256 contiguous bytes and a wave-wide ballot of a
-// per-dimension predicate *is* the 64-bit word of the bit-plane (bit l = dimension 64w+l).
+// One wavefront encodes one vector (a few consecutive ones when they are short).  Lane l of the wave
+// owns dimensions l, l+64, l+128, ..., so every load instruction reads 256 contiguous bytes and a
+// wave-wide ballot of a per-dimension predicate *is* the 64-bit word of the bit-plane (bit l = dimension 64w+l).
 //
 // The threshold test uses the exact mean: strong_i <=> d*|x_i| > sum_j |x_j| in real
 // arithmetic.  Fast path: the sum S is accumulated in double (every term is >= 0, so any
 // summation order has relative error <= (d-1)*2^-53); with margin = d*2^-52*S, a value above
 // (S+margin)/d is certainly strong and one below (S-margin)/d certainly weak.  Both bounds are
-// rounded outwards to float32 (two ulps further than round-to-nearest), so each element costs two
-// float compares.  Any vector with an element between the bounds is redone with an integer
+// rounded outwards to float32 (two ulps further than round-to-nearest, which also covers the 2^-52 of
+// forming the quotients with a precomputed 1/d), so each element costs two float compares.  Any vector with an element between the bounds is redone with an integer
 // super-accumulator in LDS.  (float32 subnormals are compared and converted as such: HIP's
 // default for gfx9 keeps them; the parity tests cover subnormal-only vectors.)
 #include <hip/hip_runtime.h>
