@@ -70,9 +70,10 @@ def main() -> int:
     ap.add_argument("--encoding", choices=("sm", "sign1", "sq2"), default="sm",
                     help="sm: the method; sign1 / sq2: the paper's ablation encodings (graph built on the GPU in that "
                          "encoding's own distance, so --graph gpu is implied and there is no CPU leg)")
-    ap.add_argument("--aligned-rows", action="store_true",
-                    help="search code rows padded to the stride at which a row touches the fewest 128-byte lines "
-                         "(only differs from dense rows at some widths, e.g. 384-d and 960-d)")
+    ap.add_argument("--index-layout", choices=("dense", "recommended"), default="dense",
+                    help="recommended: the index's code rows in the layout qv_code_layout names (planes padded to a "
+                         "compiled kernel width, rows aligned to 128-byte lines); differs from dense rows only at "
+                         "some widths, e.g. 384-d and 960-d")
     ap.add_argument("--cold-host", action="store_true",
                     help="keep the float32 vectors in pinned host memory (rerank reads them over PCIe)")
     ap.add_argument("--no-scan", action="store_true", help="skip the brute-force code scan / overlap probe")
@@ -142,9 +143,11 @@ def main() -> int:
     if args.cold_host:
         x_cold = torch.empty(x.shape, dtype=torch.float32, pin_memory=True)
         x_cold.copy_(torch.from_numpy(x))
-    stride = qv.code_stride_words(w.d, enc) if args.aligned_rows else qv.code_words(w.d, enc)
-    index_codes = qv.pad_codes(codes, w.d, stride, enc=enc) if stride != qv.code_words(w.d, enc) else codes
-    index = qv.Index(adjd, index_codes, x_cold if args.cold_host else xd, entry, enc=enc)
+    dense_layout = ((w.d + 63) // 64, qv.code_words(w.d, enc))
+    layout = qv.code_layout(w.d, enc) if args.index_layout == "recommended" else dense_layout
+    index_codes = qv.pad_codes(codes, w.d, layout, enc=enc) if layout != dense_layout else codes
+    index = qv.Index(adjd, index_codes, x_cold if args.cold_host else xd, entry, enc=enc,
+                     layout=layout if layout != dense_layout else None)
     ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
 
     # Counters for the algorithmic-byte model: one traced pass with the visited set that never forgets, which
@@ -346,7 +349,7 @@ def main() -> int:
                                        "rerank": rerank_bytes},
         "whole_path_GBps": (encq_bytes + search_bytes + rerank_bytes) / (ms_per_step * 1e-3) / 1e9,
         "encode_base": {"ms": enc_ms, "GBps": enc_bytes / enc_ms / 1e6},
-        "code_row_stride_words": stride, "graph_build_s": t_graph, "graph_from": args.graph, "encoding": args.encoding,
+        "index_code_layout": {"plane_words": layout[0], "row_stride_words": layout[1]}, "graph_build_s": t_graph, "graph_from": args.graph, "encoding": args.encoding,
         "random_row_gather_ceiling_GBps": gather_gbps,
         "search_bytes_line_granular": int(4 * w.R * n_exp.sum() + (2 * 128 if code_b % 128 else code_b) * n_eval.sum())
         if code_b <= 256 else None,

@@ -85,7 +85,7 @@ int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids
  * 2. Load (paper Sec. 4.2: hot data = codes + flat adjacency, cold data = float32 vectors).
  *    Creates a host-side handle that remembers the borrowed device buffers; copies nothing.
  *    adj    device, [n][R] uint32, QV_EMPTY = empty slot (rows need not be packed to the left)
- *    codes  device, [n][qv_code_words(d)] uint64 in qv_encode's layout (rows further apart: qv_index_set_code_stride)
+ *    codes  device, [n][qv_code_words(d)] uint64 in qv_encode's layout (or another layout: qv_index_set_code_layout)
  *    vecs   [n][d] float32, only read by the rerank: device memory, or host memory the device can address
  *           (hipHostMalloc / pinned): the paper's cold store then stays in host RAM and the rerank's ef rows per
  *           query travel over PCIe
@@ -224,24 +224,34 @@ int qv_index_set_encoding(qv_index* index, int encoding);
 int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode);
 
 /*
- * Line-aligned code rows (a memory-layout option of this library, not of the paper; Sec. 4.2 fixes only what the hot
- * data holds).  The search gathers code rows at random, and the memory system moves 128-byte lines: a 96-byte
- * row (d = 384) stored densely straddles a line boundary every other time, a 240-byte row (d = 960) touches
- * 2.75 lines on average instead of 2.  Rows stored `stride` words apart, stride * 8 a divisor or a multiple of
- * 128, touch the fewest lines there are.
- *   qv_code_stride_words  (host only) the stride, in 64-bit words, that minimises the lines per row for this d:
- *                    the dense row length when padding gains nothing (d = 768: 192 bytes are two lines either
- *                    way), else the row length rounded up to 16 / 32 / 64 bytes or to a multiple of 128 bytes.
- *                    0 on invalid arguments.
- *   qv_pad_codes     out[i*stride + w] = codes[i*words + w] for w < words = qv_code_words_enc(d, encoding),
- *                    0 in the padding.  codes: device, dense rows; out: device, n * stride words, caller's;
- *                    stride = words, or even and > words, at most 4 words + 16 (QV_ERR_INVALID_ARG otherwise).  Asynchronous on `stream`.
- *   qv_index_set_code_stride  tells an index that the rows of its `codes` are `stride` words apart (default: dense).
- *                    Only qv_search reads an index; every other entry point takes dense rows.
+ * Layout of an index's codes (an option of this library, not of the paper; Sec. 4.2 fixes only what the hot data
+ * holds).  Two things cost the search time without changing what it computes, and both are a matter of where the
+ * words of a code row sit:
+ *   - the search kernel is compiled for certain plane widths (2, 4, 6, 8, 12, 16, 24, 32, 48 words of 64 bits for
+ *     Sign-Magnitude codes); other widths (960-d = 15 words, 300-d = 5 words, ...) run a general kernel that is
+ *     about 1.7x slower.  Planes padded with zero words to the next compiled width take the fast kernel, and
+ *     zero words add nothing to any distance;
+ *   - the memory system moves 128-byte lines and rows are gathered at random: a 96-byte row (384-d) stored
+ *     densely straddles a line boundary every other time.  Rows stored `stride` words apart, stride * 8 a
+ *     divisor or a multiple of 128, touch the fewest lines there are.
+ * A layout is (plane_words, stride): row i starts at word i * stride; its plane p occupies words
+ * [p * plane_words, p * plane_words + ceil(d/64)) of the row and is followed by zero words up to plane_words.
+ *   qv_code_layout   (host only) the layout recommended for this d and encoding: plane_words = the next compiled
+ *                    width if that is at most a third more than ceil(d/64), else ceil(d/64); stride = the row
+ *                    length, rounded up to 16 / 32 / 64 bytes or a multiple of 128 bytes where that lowers the
+ *                    mean number of lines a row touches (768-d: 192 bytes are two lines either way, so dense).
+ *   qv_pad_codes     dense rows (qv_encode's layout) -> rows in the given layout.  codes: device, dense; out: device,
+ *                    n * stride words, caller's.  ceil(d/64) <= plane_words <= 1.5 ceil(d/64) + 2; stride = planes *
+ *                    plane_words, or larger and even, at most 4 planes * plane_words + 16 (QV_ERR_INVALID_ARG
+ *                    otherwise).  Asynchronous on `stream`.
+ *   qv_index_set_code_layout  tells an index that its `codes` are in this layout ((0, 0): dense, the default).  Same
+ *                    limits.  Only qv_search reads an index; every other entry point takes dense rows.  Query codes
+ *                    are brought into the same plane width inside qv_search (its workspace has room for that).
  */
-int qv_code_stride_words(int d, int encoding);
-int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int stride, uint64_t* out, void* stream);
-int qv_index_set_code_stride(qv_index* index, int stride);
+int qv_code_layout(int d, int encoding, int* plane_words, int* stride);
+int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int plane_words, int stride, uint64_t* out,
+                 void* stream);
+int qv_index_set_code_layout(qv_index* index, int plane_words, int stride);
 
 const char* qv_strerror(int code);
 const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */

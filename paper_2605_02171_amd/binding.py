@@ -84,12 +84,12 @@ _lib.qv_build_graph_enc.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_i
                                     ctypes.c_double, ctypes.c_uint32, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]
 _lib.qv_index_set_encoding.restype = ctypes.c_int
 _lib.qv_index_set_encoding.argtypes = [_P, ctypes.c_int]
-_lib.qv_code_stride_words.restype = ctypes.c_int
-_lib.qv_code_stride_words.argtypes = [ctypes.c_int, ctypes.c_int]
+_lib.qv_code_layout.restype = ctypes.c_int
+_lib.qv_code_layout.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
 _lib.qv_pad_codes.restype = ctypes.c_int
-_lib.qv_pad_codes.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _P, _P]
-_lib.qv_index_set_code_stride.restype = ctypes.c_int
-_lib.qv_index_set_code_stride.argtypes = [_P, ctypes.c_int]
+_lib.qv_pad_codes.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _P, _P]
+_lib.qv_index_set_code_layout.restype = ctypes.c_int
+_lib.qv_index_set_code_layout.argtypes = [_P, ctypes.c_int, ctypes.c_int]
 _lib.qv_search_workspace_bytes.restype = ctypes.c_size_t
 _lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search.restype = ctypes.c_int
@@ -170,19 +170,21 @@ def encode(x: torch.Tensor, want_status: bool = False, enc: int = ENC_SM):
     return (codes, status) if want_status else codes
 
 
-def code_stride_words(d: int, enc: int = ENC_SM) -> int:
-    """qv_code_stride_words: row stride (64-bit words) at which a code row touches the fewest 128-byte lines."""
-    return int(_lib.qv_code_stride_words(d, int(enc)))
+def code_layout(d: int, enc: int = ENC_SM) -> tuple[int, int]:
+    """qv_code_layout: (plane_words, stride) recommended for an index's codes (compiled plane width, line-aligned rows)."""
+    pw, st = ctypes.c_int(0), ctypes.c_int(0)
+    _check(_lib.qv_code_layout(int(d), int(enc), ctypes.byref(pw), ctypes.byref(st)), "qv_code_layout")
+    return pw.value, st.value
 
 
-def pad_codes(codes: torch.Tensor, d: int, stride: int | None = None, enc: int = ENC_SM) -> torch.Tensor:
-    """qv_pad_codes: dense [n, cw] code rows -> [n, stride] (zero padded); stride defaults to code_stride_words."""
+def pad_codes(codes: torch.Tensor, d: int, layout: tuple[int, int] | None = None, enc: int = ENC_SM) -> torch.Tensor:
+    """qv_pad_codes: dense [n, cw] code rows -> [n, stride] rows in `layout` = (plane_words, stride); default: code_layout."""
     codes = _dev(codes, torch.int64, "codes")
     if codes.dim() != 2 or codes.shape[1] != code_words(d, enc):
         raise ValueError("codes must be [n, code_words(d)]")
-    stride = code_stride_words(d, enc) if stride is None else int(stride)
+    pw, stride = code_layout(d, enc) if layout is None else (int(layout[0]), int(layout[1]))
     out = torch.empty((codes.shape[0], stride), dtype=torch.int64, device=codes.device)
-    _check(_lib.qv_pad_codes(codes.data_ptr(), codes.shape[0], d, int(enc), stride, out.data_ptr(), _stream()),
+    _check(_lib.qv_pad_codes(codes.data_ptr(), codes.shape[0], d, int(enc), pw, stride, out.data_ptr(), _stream()),
            "qv_pad_codes")
     return out
 
@@ -286,13 +288,14 @@ class Timer:
 class Index:
     """qv_index_load: borrows adj [n, R] (int32/uint32 bits), codes [n, cw] int64, vecs [n, d] float32.
 
-    codes may also be [n, stride] with stride > cw (from ``pad_codes``): the index is then told the row stride.
+    With ``layout=(plane_words, stride)`` codes is [n, stride] as ``pad_codes`` wrote it.
 
     vecs may be a device tensor or a pinned host tensor (``pin_memory=True``): the float32 vectors are the
     cold data of the method and are only touched by the rerank.
     """
 
-    def __init__(self, adj: torch.Tensor, codes: torch.Tensor, vecs: torch.Tensor, entry: int, enc: int = ENC_SM):
+    def __init__(self, adj: torch.Tensor, codes: torch.Tensor, vecs: torch.Tensor, entry: int, enc: int = ENC_SM,
+                 layout: tuple[int, int] | None = None):
         adj = _dev(adj, torch.int32, "adj")
         codes = _dev(codes, torch.int64, "codes")
         if isinstance(vecs, torch.Tensor) and not vecs.is_cuda and vecs.is_pinned():
@@ -302,7 +305,8 @@ class Index:
         else:
             vecs = _dev(vecs, torch.float32, "vecs")
         n, d = vecs.shape
-        if adj.shape[0] != n or codes.dim() != 2 or codes.shape[0] != n or codes.shape[1] < code_words(d, enc):
+        row = code_words(d, enc) if layout is None else int(layout[1])
+        if adj.shape[0] != n or codes.shape != (n, row):
             raise ValueError("adj/codes/vecs shapes do not agree")
         self.n, self.d, self.R = n, d, adj.shape[1]
         self._keep = (adj, codes, vecs)  # the library borrows these buffers
@@ -313,8 +317,8 @@ class Index:
         self._timer = None
         if enc != ENC_SM:
             _check(_lib.qv_index_set_encoding(h, int(enc)), "qv_index_set_encoding")
-        if codes.shape[1] != code_words(d, enc):
-            _check(_lib.qv_index_set_code_stride(h, int(codes.shape[1])), "qv_index_set_code_stride")
+        if layout is not None:
+            _check(_lib.qv_index_set_code_layout(h, int(layout[0]), int(layout[1])), "qv_index_set_code_layout")
 
     def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0,
                    visited_mode: int = 0) -> None:

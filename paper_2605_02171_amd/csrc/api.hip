@@ -26,13 +26,17 @@ int hip_fail(hipError_t e, const char* where) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t qcodes, cand_ids, cand_dist, n_cand, order, total;
+    size_t qcodes, qcodes_wide, cand_ids, cand_dist, n_cand, order, total;
 };
+
+// widest plane (64-bit words) an index may store for vectors of nw words per plane: half as much again, plus two
+inline int max_plane_words(int nw) { return nw + nw / 2 + 2; }
 
 WorkspaceLayout layout(int64_t nq, int d, int ef) {
     WorkspaceLayout L;
     size_t off = 0;
     L.qcodes = off;    off = align_up(off + (size_t)nq * qv_code_words(d) * 8, 256);
+    L.qcodes_wide = off; off = align_up(off + (size_t)nq * 2 * max_plane_words((d + 63) / 64) * 8, 256);   // queries in a widened index layout
     L.cand_ids = off;  off = align_up(off + (size_t)nq * ef * 4, 256);
     L.cand_dist = off; off = align_up(off + (size_t)nq * ef * 4, 256);
     L.n_cand = off;    off = align_up(off + (size_t)nq * 4, 256);
@@ -61,6 +65,7 @@ struct qv_index {
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
     int visited_mode;   // 0: choose from ef; QV_VISITED_EXACT; QV_VISITED_CACHE
     int encoding;       // QV_ENC_*: what `codes` holds and what the queries are encoded to
+    int code_plane_words;  // 64-bit words per bit-plane as stored in `codes`; 0: ceil(d / 64)
     int code_stride;    // 64-bit words between rows of `codes`; 0: dense
     qv_timer* timer;
 };
@@ -183,7 +188,7 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->encoding = QV_ENC_SM; ix->code_stride = 0; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->encoding = QV_ENC_SM; ix->code_plane_words = 0; ix->code_stride = 0; ix->timer = nullptr;
     *out = ix;
     return QV_OK;
 }
@@ -210,33 +215,56 @@ int qv_index_set_encoding(qv_index* index, int encoding) {
     return QV_OK;
 }
 
-int qv_code_stride_words(int d, int encoding) {
-    const int words = qv_code_words_enc(d, encoding);
-    if (words == 0) return 0;
-    const int bytes = words * 8;
-    // smallest stride >= the row that divides 128 or is a multiple of it
-    int padded = bytes <= 16 ? 16 : (bytes <= 32 ? 32 : (bytes <= 64 ? 64 : (bytes + 127) / 128 * 128));
-    // lines a row touches on average: dense rows start at every multiple of gcd(bytes, 128) within a line
+// lines of 128 bytes a row of `bytes` bytes touches on average when rows are `bytes` apart (dense) ...
+static double dense_lines(int bytes) {
     int g = bytes, r = 128;
-    while (r) { int t = g % r; g = r; r = t; }
-    const double dense_lines = (bytes + 128 - g) / 128.0, padded_lines = padded <= 128 ? 1.0 : padded / 128.0;
-    return padded_lines < dense_lines ? padded / 8 : words;
+    while (r) { int t = g % r; g = r; r = t; }      // rows start at every multiple of gcd(bytes, 128) within a line
+    return (bytes + 128 - g) / 128.0;
 }
 
-int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int stride, uint64_t* out, void* stream) {
-    const int words = qv_code_words_enc(d, encoding);
+int qv_code_layout(int d, int encoding, int* plane_words, int* stride) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (words == 0 || n < 0 || stride < words || (stride != words && (stride & 1)) || stride > 4 * words + 16) return QV_ERR_INVALID_ARG;
+    if (!enc_ok(encoding)) return QV_ERR_INVALID_ARG;
+    if (!plane_words || !stride) return QV_ERR_NULL;
+    const int nw = (d + 63) / 64, planes = encoding == QV_ENC_SIGN1 ? 1 : 2;
+    // planes as wide as the nearest width the search kernel is compiled for, if that costs at most a third more
+    int pw = qv::search_compiled_width_at_least(nw, encoding);
+    if (pw == 0 || 3 * pw > 4 * nw || pw > max_plane_words(nw)) pw = nw;
+    const int bytes = planes * pw * 8;
+    // smallest stride >= the row that divides 128 bytes or is a multiple of them, if rows then touch fewer lines
+    const int padded = bytes <= 16 ? 16 : (bytes <= 32 ? 32 : (bytes <= 64 ? 64 : (bytes + 127) / 128 * 128));
+    const double padded_lines = padded <= 128 ? 1.0 : padded / 128.0;
+    *plane_words = pw;
+    *stride = padded_lines < dense_lines(bytes) ? padded / 8 : planes * pw;
+    return QV_OK;
+}
+
+static bool layout_ok(int d, int encoding, int plane_words, int stride) {
+    const int nw = (d + 63) / 64, planes = encoding == QV_ENC_SIGN1 ? 1 : 2;
+    if (plane_words < nw || plane_words > max_plane_words(nw)) return false;
+    const int row = planes * plane_words;
+    return stride == row || (stride > row && !(stride & 1) && stride <= 4 * row + 16);
+}
+
+int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int plane_words, int stride, uint64_t* out,
+                 void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (!enc_ok(encoding) || n < 0 || !layout_ok(d, encoding, plane_words, stride)) return QV_ERR_INVALID_ARG;
     if (n == 0) return QV_OK;
     if (!codes || !out) return QV_ERR_NULL;
-    hipError_t e = qv::launch_pad_codes(codes, n, words, stride, out, (hipStream_t)stream);
+    hipError_t e = qv::launch_pad_codes(codes, n, (d + 63) / 64, encoding == QV_ENC_SIGN1 ? 1 : 2, plane_words, stride, out,
+                                        (hipStream_t)stream);
     return e == hipSuccess ? QV_OK : hip_fail(e, "code padding launch");
 }
 
-int qv_index_set_code_stride(qv_index* index, int stride) {
+int qv_index_set_code_layout(qv_index* index, int plane_words, int stride) {
     if (!index) return QV_ERR_NULL;
-    const int words = qv_code_words_enc(index->d, index->encoding);
-    if (stride != 0 && (stride < words || (stride != words && (stride & 1)) || stride > 4 * words + 16)) return QV_ERR_INVALID_ARG;
+    if (plane_words == 0 && stride == 0) {   // back to dense rows
+        index->code_plane_words = index->code_stride = 0;
+        return QV_OK;
+    }
+    if (!layout_ok(index->d, index->encoding, plane_words, stride)) return QV_ERR_INVALID_ARG;
+    index->code_plane_words = plane_words;
     index->code_stride = stride;
     return QV_OK;
 }
@@ -261,24 +289,35 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     char* ws = static_cast<char*>(workspace);
     uint64_t* qcodes = reinterpret_cast<uint64_t*>(ws + L.qcodes);
 
+    const int nw = (index->d + 63) / 64, planes = index->encoding == QV_ENC_SIGN1 ? 1 : 2;
+    int plane_words = nw, row_stride = planes * nw;
+    if (index->code_stride > 0) {
+        if (!layout_ok(index->d, index->encoding, index->code_plane_words, index->code_stride))
+            return QV_ERR_INVALID_ARG;  // the layout was set before the encoding changed
+        plane_words = index->code_plane_words;
+        row_stride = index->code_stride;
+    }
+
     qv_timer* tm = index->timer;
     hipEvent_t* ev = nullptr;
     if (tm && tm->used < tm->max_calls) ev = tm->ev + 4 * (size_t)tm->used++;
     hipError_t e;
     if (ev && (e = hipEventRecord(ev[0], stream)) != hipSuccess) return hip_fail(e, "event record");
 
-    // Stage 1 preamble: the query's own code
+    // Stage 1 preamble: the query's own code, then (index stored with wider planes) the same words in that layout
     e = qv::launch_encode(queries, nq, index->d, index->encoding, qcodes, nullptr, stream);
     if (e != hipSuccess) return hip_fail(e, "query encode launch");
+    if (plane_words != nw) {
+        uint64_t* wide = reinterpret_cast<uint64_t*>(ws + L.qcodes_wide);
+        e = qv::launch_pad_codes(qcodes, nq, nw, planes, plane_words, planes * plane_words, wide, stream);
+        if (e != hipSuccess) return hip_fail(e, "query code layout launch");
+        qcodes = wide;
+    }
 
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes; sp.encoding = index->encoding;
-    sp.row_stride = qv::code_row_words((index->d + 63) / 64, index->encoding);
-    if (index->code_stride > 0) {
-        if (index->code_stride < sp.row_stride) return QV_ERR_INVALID_ARG;  // set before the encoding changed
-        sp.row_stride = index->code_stride;
-    }
-    sp.n = index->n; sp.nq = nq; sp.nw = (index->d + 63) / 64; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
+    sp.row_stride = row_stride;
+    sp.n = index->n; sp.nq = nq; sp.nw = plane_words; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
     // Visited set.  Default: a cache of 4096 slots (8 KB of 16-bit tags): with the list and the merge area a
     // query then needs about 10 KB of LDS, so 16 queries fit a compute unit and registers, not LDS, bound the
     // occupancy; at the beam widths of interest it forgets few ids (about 1 % more distance evaluations at

@@ -359,22 +359,25 @@ __global__ __launch_bounds__(64) void gather_probe_kernel(const uint64_t* __rest
     if (acc == 0x0123456789ABCDEFull) sink[0] = acc;  // keeps the loads alive
 }
 
-// Copies dense code rows into rows `stride` words apart (padding zeroed): one thread per output word.
-__global__ __launch_bounds__(256) void pad_codes_kernel(const uint64_t* __restrict__ codes, int64_t n, int words, int stride,
-                                                        uint64_t* __restrict__ out) {
+// Copies dense code rows (planes of nw words) into rows `stride` words apart whose planes are plane_words long;
+// everything that is not a code word is zero.  One thread per output word.
+__global__ __launch_bounds__(256) void pad_codes_kernel(const uint64_t* __restrict__ codes, int64_t n, int nw, int planes,
+                                                        int plane_words, int stride, uint64_t* __restrict__ out) {
     const int64_t total = n * stride;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
         const int64_t row = i / stride;
-        const int w = (int)(i - row * stride);
-        out[i] = w < words ? codes[row * words + w] : 0ull;
+        const int at = (int)(i - row * stride);
+        const int plane = at / plane_words, w = at - plane * plane_words;
+        out[i] = (plane < planes && w < nw) ? codes[row * (planes * nw) + plane * nw + w] : 0ull;
     }
 }
 
-hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int words, int stride, uint64_t* out, hipStream_t stream) {
+hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int nw, int planes, int plane_words, int stride, uint64_t* out,
+                            hipStream_t stream) {
     if (n == 0) return hipSuccess;
     int64_t blocks = (n * stride + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
-    hipLaunchKernelGGL(pad_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, codes, n, words, stride, out);
+    hipLaunchKernelGGL(pad_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, codes, n, nw, planes, plane_words, stride, out);
     return hipGetLastError();
 }
 

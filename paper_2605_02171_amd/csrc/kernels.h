@@ -22,7 +22,7 @@ struct SearchParams {
     int row_stride;          // 64-bit words between the rows of `codes` (even, >= the row's words); qcodes are dense
     int64_t n;
     int64_t nq;
-    int nw;                  // 64-bit words per bit-plane
+    int nw;                  // 64-bit words per bit-plane as stored (codes and qcodes alike; >= ceil(d / 64), zero padded)
     int R;
     uint32_t entry;
     int ef;
@@ -58,7 +58,9 @@ struct RerankParams {
 
 hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_t* codes, uint32_t* status,
                          hipStream_t stream);
-hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int words, int stride, uint64_t* out, hipStream_t stream);
+// dense code rows (planes of nw words) -> rows `stride` words apart whose planes are plane_words long (zero filled)
+hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int nw, int planes, int plane_words, int stride, uint64_t* out,
+                            hipStream_t stream);
 hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
                               int64_t npairs, int d, int encoding, uint32_t* out, hipStream_t stream);
 hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
@@ -72,6 +74,8 @@ bool build_supports_width(int nw, int encoding);
 size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch);
 hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream);
+// smallest plane width >= nw the search kernel is compiled for with this encoding; 0 if there is none
+int search_compiled_width_at_least(int nw, int encoding);
 // lanes_per_row: 0 = pick from the shape
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream);
 // Fills order[nq] with a launch order of the queries: those whose code is farthest from the entry node's code

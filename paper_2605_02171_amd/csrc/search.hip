@@ -841,10 +841,23 @@ hipError_t launch_beam_search_w(const SearchParams& p, int g, hipStream_t stream
 template hipError_t launch_beam_search_w<QV_SEARCH_ENC, QV_SEARCH_WIDTH>(const SearchParams& p, int g, hipStream_t stream);
 
 #if QV_SEARCH_WIDTH == 0 && QV_SEARCH_ENC == 0
+// plane widths (64-bit words) the Sign-Magnitude search kernel is compiled for; build.py compiles one object per entry
+#define QV_SM_WIDTHS(X) X(2) X(4) X(6) X(8) X(12) X(16) X(24) X(32) X(48)
+#define QV_EXT_SM(W) extern template hipError_t launch_beam_search_w<ENC_SM, W>(const SearchParams&, int, hipStream_t);
+QV_SM_WIDTHS(QV_EXT_SM)
+#undef QV_EXT_SM
 #define QV_EXT(E, W) extern template hipError_t launch_beam_search_w<E, W>(const SearchParams&, int, hipStream_t);
-QV_EXT(ENC_SM, 2) QV_EXT(ENC_SM, 6) QV_EXT(ENC_SM, 8) QV_EXT(ENC_SM, 12) QV_EXT(ENC_SM, 16) QV_EXT(ENC_SM, 24) QV_EXT(ENC_SM, 48)
 QV_EXT(ENC_SIGN1, 0) QV_EXT(ENC_SIGN1, 12) QV_EXT(ENC_SQ2, 0) QV_EXT(ENC_SQ2, 12)
 #undef QV_EXT
+
+int search_compiled_width_at_least(int nw, int encoding) {
+    if (encoding != ENC_SM) return nw <= 12 ? 12 : 0;
+    int best = 0;
+#define QV_PICK(W) if (best == 0 && W >= nw) best = W;
+    QV_SM_WIDTHS(QV_PICK)
+#undef QV_PICK
+    return best;
+}
 
 hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStream_t stream) {
     if (p.nq == 0) return hipSuccess;
@@ -855,13 +868,9 @@ hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStrea
     if (p.encoding == ENC_SQ2)
         return p.nw == 12 ? launch_beam_search_w<ENC_SQ2, 12>(p, g, stream) : launch_beam_search_w<ENC_SQ2, 0>(p, g, stream);
     switch (p.nw) {
-        case 2: return launch_beam_search_w<ENC_SM, 2>(p, g, stream);
-        case 6: return launch_beam_search_w<ENC_SM, 6>(p, g, stream);
-        case 8: return launch_beam_search_w<ENC_SM, 8>(p, g, stream);
-        case 12: return launch_beam_search_w<ENC_SM, 12>(p, g, stream);
-        case 16: return launch_beam_search_w<ENC_SM, 16>(p, g, stream);
-        case 24: return launch_beam_search_w<ENC_SM, 24>(p, g, stream);
-        case 48: return launch_beam_search_w<ENC_SM, 48>(p, g, stream);
+#define QV_CASE(W) case W: return launch_beam_search_w<ENC_SM, W>(p, g, stream);
+        QV_SM_WIDTHS(QV_CASE)
+#undef QV_CASE
         default: return launch_beam_search_w<ENC_SM, 0>(p, g, stream);
     }
 }

@@ -51,15 +51,31 @@ def test_sizes(lib):
     assert f(10, 768, 65, 64) == 0 and f(10, 0, 1, 8) == 0 and f(10, 768, 1, 2000) == 0 and f(-1, 8, 1, 8) == 0
 
 
-def test_line_aligned_row_strides(lib):
-    """The recommended stride is the dense row unless padding lowers the mean number of 128-byte lines a row
-    touches; check that against a brute-force count over every row offset."""
-    f = lib.qv_code_stride_words
+def _compiled_widths():
+    """Plane widths the Sign-Magnitude search kernel is compiled for, from the source's own list."""
+    src = open(os.path.join(ROOT, "paper_2605_02171_amd", "csrc", "search.hip")).read()
+    line = re.search(r"#define QV_SM_WIDTHS\(X\)(.*)", src).group(1)
+    return sorted(int(w) for w in re.findall(r"X\((\d+)\)", line))
+
+
+def test_build_script_compiles_every_width_the_dispatcher_names():
+    from paper_2605_02171_amd import build
+    sm = sorted(w for e, w in build.SEARCH_VARIANTS if e == 0 and w != 0)
+    assert sm == _compiled_widths()
+    assert {(1, 0), (1, 12), (2, 0), (2, 12), (0, 0)} <= set(build.SEARCH_VARIANTS)
+
+
+def test_recommended_code_layout(lib):
+    """Planes go to the next compiled width when that costs at most a third more; the stride is the row unless
+    padding lowers the mean number of 128-byte lines a row touches (checked by counting over every row offset)."""
+    f = lib.qv_code_layout
     f.restype = ctypes.c_int
-    f.argtypes = [ctypes.c_int, ctypes.c_int]
-    g = lib.qv_code_words_enc
-    g.restype = ctypes.c_int
-    g.argtypes = [ctypes.c_int, ctypes.c_int]
+    f.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+
+    def layout(d, enc):
+        pw, st = ctypes.c_int(-1), ctypes.c_int(-1)
+        assert f(d, enc, ctypes.byref(pw), ctypes.byref(st)) == 0
+        return pw.value, st.value
 
     def mean_lines(row_bytes, stride_bytes):
         total = 0
@@ -68,20 +84,33 @@ def test_line_aligned_row_strides(lib):
             total += (a + row_bytes - 1) // 128 - a // 128 + 1
         return total / 128
 
-    assert [f(d, 0) for d in (64, 128, 192, 384, 512, 768, 960, 1024, 3072)] == [2, 4, 8, 16, 16, 24, 32, 32, 96]
-    assert [f(d, 1) for d in (64, 192, 384, 768, 960)] == [1, 4, 8, 16, 16]
-    assert f(0, 0) == 0 and f(768, 9) == 0 and f(70000, 0) == 0
+    assert [layout(d, 0) for d in (64, 128, 192, 300, 384, 448, 512, 768, 960, 1024, 1100, 1536, 2048, 3072, 4096)] == \
+        [(1, 2), (2, 4), (4, 8), (6, 16), (6, 16), (8, 16), (8, 16), (12, 24), (16, 32), (16, 32), (24, 48), (24, 48),
+         (32, 64), (48, 96), (64, 128)]
+    assert [layout(d, 1) for d in (64, 192, 384, 700, 768, 960)] == [(1, 1), (3, 4), (6, 8), (12, 16), (12, 16), (15, 16)]
+    assert [layout(d, 2) for d in (384, 700, 768)] == [(6, 16), (12, 24), (12, 24)]
+    pw, st = ctypes.c_int(0), ctypes.c_int(0)
+    assert f(0, 0, ctypes.byref(pw), ctypes.byref(st)) == -3 and f(70000, 0, ctypes.byref(pw), ctypes.byref(st)) == -3
+    assert f(768, 9, ctypes.byref(pw), ctypes.byref(st)) == -1 and f(768, 0, None, ctypes.byref(st)) == -2
+    widths = _compiled_widths()
     for enc in (0, 1, 2):
-        for d in list(range(1, 2200, 37)) + [64, 384, 768, 960, 1024, 1536, 3072, 65536]:
-            words, stride = g(d, enc), f(d, enc)
-            assert stride >= words and (stride == words or stride % 2 == 0) and stride <= 4 * words + 16
-            dense, chosen = mean_lines(words * 8, words * 8), mean_lines(words * 8, stride * 8)
+        planes = 1 if enc == 1 else 2
+        for d in list(range(1, 3300, 41)) + [64, 384, 768, 960, 1024, 1536, 3072, 65536]:
+            nw = (d + 63) // 64
+            pw, stride = layout(d, enc)
+            assert nw <= pw <= nw + nw // 2 + 2 and 3 * pw <= 4 * nw or pw == nw
+            if enc == 0:
+                nxt = next((w for w in widths if w >= nw), 0)
+                assert pw == (nxt if nxt and 3 * nxt <= 4 * nw else nw)
+            row = planes * pw
+            assert stride >= row and (stride == row or stride % 2 == 0) and stride <= 4 * row + 16
+            dense, chosen = mean_lines(row * 8, row * 8), mean_lines(row * 8, stride * 8)
             assert chosen <= dense
-            if stride != words:
+            if stride != row:
                 assert chosen < dense                                      # padding only when it pays
-                assert chosen == max(1, -(-words * 8 // 128))             # and then a row touches the fewest lines possible
+                assert chosen == max(1, -(-row * 8 // 128))               # and then a row touches the fewest lines possible
             else:                                                          # no aligned stride would do better
-                bytes_ = words * 8
+                bytes_ = row * 8
                 aligned = next(s for s in (16, 32, 64) if s >= bytes_) if bytes_ <= 64 else -(-bytes_ // 128) * 128
                 assert mean_lines(bytes_, aligned) >= dense
 
@@ -121,19 +150,21 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_index_set_tuning(h, 512, 0, 0, 0) == -1 and lib.qv_index_set_tuning(h, 0, 3, 0, 0) == -1
     assert lib.qv_index_set_tuning(h, 0, 0, 16, 0) == -1 and lib.qv_index_set_tuning(h, 8192, 4, 32, 0) == 0
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 3) == -1 and lib.qv_index_set_tuning(h, 4096, 2, 0, 2) == 0
-    # row stride of the index's codes: the dense length, or even and longer (d = 8: one word per plane, 2 per row)
-    lib.qv_index_set_code_stride.argtypes = [P, ctypes.c_int]
-    assert lib.qv_index_set_code_stride(h, 0) == 0 and lib.qv_index_set_code_stride(h, 2) == 0
-    assert lib.qv_index_set_code_stride(h, 4) == 0 and lib.qv_index_set_code_stride(h, 16) == 0
-    assert lib.qv_index_set_code_stride(h, 1) == -1 and lib.qv_index_set_code_stride(h, 3) == -1
-    assert lib.qv_index_set_code_stride(h, 4096) == -1 and lib.qv_index_set_code_stride(None, 2) == -2
-    lib.qv_pad_codes.argtypes = [P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P]
-    assert lib.qv_pad_codes(fake, 5, 384, 0, 11, fake, None) == -1       # shorter than the row
-    assert lib.qv_pad_codes(fake, 5, 384, 0, 13, fake, None) == -1       # odd
-    assert lib.qv_pad_codes(fake, 5, 384, 7, 16, fake, None) == -1       # unknown encoding
-    assert lib.qv_pad_codes(fake, 5, 0, 0, 16, fake, None) == -3
-    assert lib.qv_pad_codes(None, 5, 384, 0, 16, fake, None) == -2
-    assert lib.qv_pad_codes(None, 0, 384, 0, 16, None, None) == 0        # nothing to do
+    # layout of the index's codes (d = 8: one word per plane, two planes)
+    lib.qv_index_set_code_layout.argtypes = [P, ctypes.c_int, ctypes.c_int]
+    ok = lib.qv_index_set_code_layout
+    assert ok(h, 0, 0) == 0 and ok(h, 1, 2) == 0 and ok(h, 1, 4) == 0 and ok(h, 2, 4) == 0 and ok(h, 3, 16) == 0
+    assert ok(h, 1, 1) == -1 and ok(h, 1, 3) == -1 and ok(h, 2, 2) == -1 and ok(h, 4, 8) == -1 and ok(h, 0, 2) == -1
+    assert ok(h, 1, 4096) == -1 and ok(None, 1, 2) == -2
+    lib.qv_pad_codes.argtypes = [P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P]
+    assert lib.qv_pad_codes(fake, 5, 384, 0, 5, 16, fake, None) == -1      # planes shorter than the code's
+    assert lib.qv_pad_codes(fake, 5, 384, 0, 6, 11, fake, None) == -1      # rows shorter than two planes
+    assert lib.qv_pad_codes(fake, 5, 384, 0, 6, 13, fake, None) == -1      # odd
+    assert lib.qv_pad_codes(fake, 5, 384, 0, 12, 24, fake, None) == -1     # planes more than half as wide again + 2
+    assert lib.qv_pad_codes(fake, 5, 384, 7, 6, 16, fake, None) == -1      # unknown encoding
+    assert lib.qv_pad_codes(fake, 5, 0, 0, 6, 16, fake, None) == -3
+    assert lib.qv_pad_codes(None, 5, 384, 0, 6, 16, fake, None) == -2
+    assert lib.qv_pad_codes(None, 0, 384, 0, 6, 16, None, None) == 0       # nothing to do
     lib.qv_index_free.argtypes = [P]
     lib.qv_index_free(h)
     lib.qv_index_free(None)

@@ -116,8 +116,9 @@ def _full_case(qv, name, efs, n_sample, L=None, R=None, aligned_rows=False):
         # the same batch through code rows padded to whole 128-byte lines: the sample against the oracle again,
         # the rest of the batch against the properties above by way of the dense run's lists
         ef = efs[-1]
-        util.note(f"{name}: ef={ef} with line-aligned code rows (stride {qv.code_stride_words(w.d)} words)")
-        index2 = qv.Index(qv.from_numpy_u32(adj), qv.pad_codes(gcodes, w.d), xd, entry)
+        lay = qv.code_layout(w.d)
+        util.note(f"{name}: ef={ef} with the recommended index layout (planes of {lay[0]} words, rows {lay[1]} words apart)")
+        index2 = qv.Index(qv.from_numpy_u32(adj), qv.pad_codes(gcodes, w.d, lay), xd, entry, layout=lay)
         out2 = qv.search(index2, qd, w.k, ef, trace=True, visit_cap=256)
         torch.cuda.synchronize()
         cid2, cds2 = qv.to_numpy_u32(out2.cand_ids), qv.to_numpy_u32(out2.cand_dist)

@@ -286,11 +286,16 @@ def test_search_batches_around_the_launch_order_threshold(qv, nq):
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
-@pytest.mark.parametrize("d,stride,enc,nq", [(384, None, 0, 37), (960, None, 0, 37), (100, 6, 0, 37), (768, 32, 0, 37),
-                                             (192, None, 1, 37), (384, None, 2, 37), (384, None, 0, 4200)])
-def test_search_with_line_aligned_code_rows(qv, d, stride, enc, nq):
-    """Code rows stored further apart than their length (padding zeroed): the padded copy is the dense
-    one row by row, and the search through it returns what the oracle returns on dense rows."""
+@pytest.mark.parametrize("d,layout,enc,nq", [(384, None, 0, 37), (960, None, 0, 37), (300, None, 0, 37), (448, None, 0, 37),
+                                             (1100, None, 0, 37), (2048, (32, 80), 0, 37), (200, (6, 12), 0, 37),
+                                             (100, (2, 6), 0, 37), (100, (4, 8), 0, 37), (768, (12, 32), 0, 37),
+                                             (768, (16, 32), 0, 37), (960, (15, 32), 0, 37), (1000, (24, 48), 0, 37),
+                                             (192, None, 1, 37), (700, None, 1, 37), (384, None, 2, 37), (700, None, 2, 37),
+                                             (384, None, 0, 4200), (960, None, 0, 4200)])
+def test_search_with_another_code_layout(qv, d, layout, enc, nq):
+    """Index codes with planes padded by zero words and rows further apart than their length: the re-laid-out
+    copy holds the dense code's words where the layout says, zeros elsewhere, and the search through it returns
+    what the oracle returns on dense rows."""
     rng = np.random.default_rng(d + 7 * enc)
     n, R, ef, k = 3000, 32, 48, 10
     x = rng.standard_normal((n, d)).astype(np.float32)
@@ -299,14 +304,19 @@ def test_search_with_line_aligned_code_rows(qv, d, stride, enc, nq):
     codes = oracle.encode(x, threads=8, enc=enc)
     ref = oracle.search(q, adj, codes, x, 11, k, ef, visit_cap=200, threads=8, enc=enc)
     xd = torch.from_numpy(x).cuda()
-    words = qv.code_words(d, enc)
-    if stride is None:
-        stride = qv.code_stride_words(d, enc)
-        assert stride > words                       # these widths are the ones padding helps
-    padded = qv.pad_codes(qv.encode(xd, enc=enc), d, stride, enc=enc)
+    nw, planes = (d + 63) // 64, (1 if enc == qv.ENC_SIGN1 else 2)
+    if layout is None:
+        layout = qv.code_layout(d, enc)
+        assert layout != (nw, planes * nw)          # these widths are the ones another layout helps
+    pw, stride = layout
+    padded = qv.pad_codes(qv.encode(xd, enc=enc), d, layout, enc=enc)
     got = qv.to_numpy_u64(padded)
-    assert got.shape == (n, stride) and (got[:, :words] == codes).all() and (got[:, words:] == 0).all()
-    index = qv.Index(qv.from_numpy_u32(adj), padded, xd, 11, enc=enc)
+    assert got.shape == (n, stride)
+    want = np.zeros((n, stride), dtype=np.uint64)
+    for p in range(planes):
+        want[:, p * pw:p * pw + nw] = codes[:, p * nw:(p + 1) * nw]
+    assert (got == want).all()
+    index = qv.Index(qv.from_numpy_u32(adj), padded, xd, 11, enc=enc, layout=layout)
     qd = torch.from_numpy(q).cuda()
     for mode in (qv.VISITED_CACHE, qv.VISITED_EXACT):
         index.set_tuning(0, 0, 0, mode)
