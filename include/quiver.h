@@ -170,12 +170,14 @@ int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uin
  * selecting nodes (at most the 192 nearest per batch) into its row if they fit and re-selects the row
  * from (old row U new candidates) otherwise.  The order of ids inside a row carries no meaning.
  *    codes   device, [n][qv_code_words(d)]         adj  device, [n][R] uint32, written in full
- *    1 <= R <= 64, 1 <= L <= 192, alpha >= 1, entry < n; ceil(d/64) must be one of 2, 6, 8, 12, 16
- *    (d = 65..128, 321..384, 449..512, 705..768, 961..1024); other widths: QV_ERR_UNSUPPORTED
+ *    1 <= R <= 64, 1 <= L <= 192, alpha >= 1, entry < n; d <= 1536 (planes of up to 24 words: the selection
+ *    kernels keep a whole code in registers; wider: QV_ERR_UNSUPPORTED).  The kernels are compiled for planes of
+ *    2, 4, 6, 8, 12, 16 and 24 words; codes of another width are copied into the workspace with zero words
+ *    appended to every plane (n more rows of the next compiled width), which changes no distance.
  *    workspace device, 256-byte aligned, >= qv_build_workspace_bytes(n, d, R, L, max_batch)
  * All work is queued on `stream`; the call returns when everything is queued.
  */
-size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch);
+size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch);   /* 0: arguments out of range */
 int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
                    int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -190,8 +192,9 @@ int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double
  *                  this form (a constant vector has level 3 everywhere).  Two bit-planes, low bit of the level
  *                  first, packed like the Sign-Magnitude planes.
  * qv_index_set_encoding tells an index which encoding its `codes` are in (queries are then encoded the same way).
- * Widths: encode, distance, scan and search take any d; qv_build_graph_enc takes d = 65..128 and 705..768 for the
- * two ablation encodings (QV_ERR_UNSUPPORTED otherwise).  An unknown encoding is QV_ERR_INVALID_ARG (0 words from
+ * Widths: encode, distance, scan and search take any d; qv_build_graph_enc takes d <= 768 for the two ablation
+ * encodings (compiled for planes of 2 and 12 words, other widths zero-padded in the workspace; wider:
+ * QV_ERR_UNSUPPORTED); its workspace is qv_build_workspace_bytes_enc.  An unknown encoding is QV_ERR_INVALID_ARG (0 words from
  * qv_code_words_enc).
  */
 #define QV_ENC_SM 0
@@ -203,6 +206,7 @@ int qv_bq_distance_enc(const uint64_t* codes_a, const int64_t* ia, const uint64_
                        int64_t npairs, int d, int encoding, uint32_t* out, void* stream);
 int qv_bq_scan_enc(const uint64_t* codes, int64_t n, int d, int encoding, const uint64_t* qcodes, int64_t nq, int K,
                    uint32_t* ids, uint32_t* dist, void* workspace, size_t workspace_bytes, void* stream);
+size_t qv_build_workspace_bytes_enc(int64_t n, int d, int encoding, int R, int L, int64_t max_batch);
 int qv_build_graph_enc(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream);
 int qv_index_set_encoding(qv_index* index, int encoding);

@@ -60,6 +60,8 @@ _lib.qv_topk_overlap.restype = ctypes.c_int
 _lib.qv_topk_overlap.argtypes = [_P, _P, ctypes.c_int64, ctypes.c_int, _P, _P]
 _lib.qv_build_workspace_bytes.restype = ctypes.c_size_t
 _lib.qv_build_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64]
+_lib.qv_build_workspace_bytes_enc.restype = ctypes.c_size_t
+_lib.qv_build_workspace_bytes_enc.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64]
 _lib.qv_build_graph.restype = ctypes.c_int
 _lib.qv_build_graph.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
                                 ctypes.c_uint32, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]
@@ -253,7 +255,7 @@ def build_graph(codes: torch.Tensor, d: int, R: int, L: int, alpha: float, entry
     n = codes.shape[0]
     if codes.shape[1] != code_words(d, enc):
         raise ValueError("code width does not match d")
-    need = int(_lib.qv_build_workspace_bytes(n, int(d), int(R), int(L), int(max_batch)))
+    need = int(_lib.qv_build_workspace_bytes_enc(n, int(d), int(enc), int(R), int(L), int(max_batch)))
     ws = torch.empty((max(need, 256),), dtype=torch.uint8, device=codes.device)
     adj = torch.empty((n, R), dtype=torch.int32, device=codes.device)
     _check(_lib.qv_build_graph_enc(codes.data_ptr(), n, int(d), int(enc), int(R), int(L), float(alpha), int(entry),

@@ -156,8 +156,13 @@ static bool build_args_ok(int64_t n, int d, int R, int L) {
 }
 
 size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch) {
-    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !qv::build_supports_width((d + 63) / 64, QV_ENC_SM)) return 0;
-    return qv::build_workspace_bytes(n, R, L, max_batch);
+    return qv_build_workspace_bytes_enc(n, d, QV_ENC_SM, R, L, max_batch);
+}
+
+size_t qv_build_workspace_bytes_enc(int64_t n, int d, int encoding, int R, int L, int64_t max_batch) {
+    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !enc_ok(encoding)) return 0;
+    if (qv::build_width_at_least((d + 63) / 64, encoding) == 0) return 0;
+    return qv::build_workspace_bytes(n, (d + 63) / 64, encoding, R, L, max_batch);
 }
 
 int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double alpha, uint32_t entry,
@@ -170,9 +175,9 @@ int qv_build_graph_enc(const uint64_t* codes, int64_t n, int d, int encoding, in
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
     if (!build_args_ok(n, d, R, L) || max_batch < 1 || !(alpha >= 1.0) || (int64_t)entry >= n || !enc_ok(encoding))
         return QV_ERR_INVALID_ARG;
-    if (!qv::build_supports_width((d + 63) / 64, encoding)) return QV_ERR_UNSUPPORTED;
+    if (qv::build_width_at_least((d + 63) / 64, encoding) == 0) return QV_ERR_UNSUPPORTED;
     if (!codes || !adj) return QV_ERR_NULL;
-    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < qv::build_workspace_bytes(n, R, L, max_batch))
+    if (!workspace || ((uintptr_t)workspace & 255u) || workspace_bytes < qv::build_workspace_bytes(n, (d + 63) / 64, encoding, R, L, max_batch))
         return QV_ERR_WORKSPACE;
     hipError_t e = qv::build_graph(codes, n, d, encoding, R, L, alpha, entry, max_batch, adj, workspace, (hipStream_t)stream);
     return e == hipSuccess ? QV_OK : hip_fail(e, "graph construction");

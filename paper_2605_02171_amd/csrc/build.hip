@@ -255,9 +255,17 @@ size_t build_sort_temp_bytes(int64_t max_pairs) {
     return bytes;
 }
 
-bool build_supports_width(int nw, int encoding) {
-    if (encoding != ENC_SM) return nw == 2 || nw == 12;
-    return nw == 2 || nw == 6 || nw == 8 || nw == 12 || nw == 16;
+// plane widths (64-bit words) the selection kernels are compiled for (a lane keeps a whole code in registers: 4 x width
+// of them, which ends at 24 words); codes of other widths are zero-padded to the next one in the workspace
+#define QV_BUILD_SM_WIDTHS(X) X(2) X(4) X(6) X(8) X(12) X(16) X(24)
+
+int build_width_at_least(int nw, int encoding) {
+    if (encoding != ENC_SM) return nw <= 2 ? 2 : (nw <= 12 ? 12 : 0);
+    int best = 0;
+#define QV_PICK(W) if (best == 0 && W >= nw) best = W;
+    QV_BUILD_SM_WIDTHS(QV_PICK)
+#undef QV_PICK
+    return best;
 }
 
 template <int ENC, int NW_T>
@@ -286,11 +294,9 @@ hipError_t launch_build_batch(int nw, int encoding, const BuildParams& bp, uint6
         return hipErrorInvalidValue;
     }
     switch (nw) {
-        case 2: return launch_batch<ENC_SM, 2>(bp, sorted, temp, temp_bytes, stream);
-        case 6: return launch_batch<ENC_SM, 6>(bp, sorted, temp, temp_bytes, stream);
-        case 8: return launch_batch<ENC_SM, 8>(bp, sorted, temp, temp_bytes, stream);
-        case 12: return launch_batch<ENC_SM, 12>(bp, sorted, temp, temp_bytes, stream);
-        case 16: return launch_batch<ENC_SM, 16>(bp, sorted, temp, temp_bytes, stream);
+#define QV_CASE(W) case W: return launch_batch<ENC_SM, W>(bp, sorted, temp, temp_bytes, stream);
+        QV_BUILD_SM_WIDTHS(QV_CASE)
+#undef QV_CASE
         default: return hipErrorInvalidValue;
     }
 }
@@ -306,17 +312,34 @@ int64_t build_max_batch(int64_t n, int64_t max_batch) {
     return b;
 }
 
-size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch) {
+// bytes of the zero-padded copy of the codes (0 when the width is compiled for as it is)
+static size_t padded_codes_bytes(int64_t n, int nw, int encoding) {
+    const int pw = build_width_at_least(nw, encoding);
+    return pw == nw ? 0 : up256((size_t)n * code_row_words(pw, encoding) * 8);
+}
+
+size_t build_workspace_bytes(int64_t n, int nw, int encoding, int R, int L, int64_t max_batch) {
     const int64_t mb = build_max_batch(n, max_batch);
     return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 8) * 2 +
-           up256(build_sort_temp_bytes(mb * R)) + 256;
+           up256(build_sort_temp_bytes(mb * R)) + padded_codes_bytes(n, nw, encoding) + 256;
 }
 
 hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream) {
-    const int nw = (d + 63) / 64;
+    int nw = (d + 63) / 64;
     const int64_t mb = build_max_batch(n, max_batch);
     char* ws = static_cast<char*>(workspace);
+    hipError_t e;
+    if (const int pw = build_width_at_least(nw, encoding); pw != nw) {
+        // planes padded with zero words to a width the selection kernels are compiled for: no distance changes
+        if (pw == 0) return hipErrorInvalidValue;
+        uint64_t* padded = reinterpret_cast<uint64_t*>(ws);
+        ws += padded_codes_bytes(n, nw, encoding);
+        e = launch_pad_codes(codes, n, nw, encoding == ENC_SIGN1 ? 1 : 2, pw, code_row_words(pw, encoding), padded, stream);
+        if (e != hipSuccess) return e;
+        codes = padded;
+        nw = pw;
+    }
     uint32_t* cand_ids = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * L * 4);
     uint32_t* cand_dist = reinterpret_cast<uint32_t*>(ws);  ws += up256((size_t)mb * L * 4);
     uint32_t* n_cand = reinterpret_cast<uint32_t*>(ws);     ws += up256((size_t)mb * 4);
@@ -332,7 +355,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
         const unsigned blocks = (unsigned)((words + 256 * 8 - 1) / (256 * 8) < 256 * 16 ? (words + 256 * 8 - 1) / (256 * 8) : 256 * 16);
         hipLaunchKernelGGL(fill_empty_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, adj, words);
     }
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     SearchParams sp{};
     sp.adj = adj; sp.codes = codes; sp.encoding = encoding; sp.row_stride = code_row_words(nw, encoding); sp.n = n; sp.nw = nw; sp.R = R; sp.entry = entry; sp.ef = L;

@@ -70,8 +70,9 @@ hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, int encoding,
                           uint64_t* partial, uint32_t* ids, uint32_t* dist, hipStream_t stream);
 hipError_t launch_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uint32_t* out,
                                hipStream_t stream);
-bool build_supports_width(int nw, int encoding);
-size_t build_workspace_bytes(int64_t n, int R, int L, int64_t max_batch);
+// smallest plane width >= nw the construction kernels are compiled for with this encoding; 0 if there is none
+int build_width_at_least(int nw, int encoding);
+size_t build_workspace_bytes(int64_t n, int nw, int encoding, int R, int L, int64_t max_batch);
 hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, hipStream_t stream);
 // smallest plane width >= nw the search kernel is compiled for with this encoding; 0 if there is none

@@ -138,7 +138,8 @@ def _sorted_rows(adj):
 
 @pytest.mark.parametrize("enc", ENCODINGS)
 @pytest.mark.parametrize("n,d,R,L,alpha,entry", [(1500, 128, 16, 32, 1.2, 7), (600, 128, 64, 128, 1.2, 11),
-                                                 (300, 768, 16, 48, 1.2, 299), (2500, 100, 8, 16, 1.0, 5)])
+                                                 (300, 768, 16, 48, 1.2, 299), (2500, 100, 8, 16, 1.0, 5),
+                                                 (800, 300, 16, 32, 1.2, 3), (500, 40, 8, 16, 1.2, 0)])
 def test_build_matches_oracle(qv, enc, n, d, R, L, alpha, entry):
     rng = np.random.default_rng(n + d + enc)
     x = rng.standard_normal((n, d)).astype(np.float32)
@@ -157,8 +158,8 @@ def test_argument_errors(qv):
     with pytest.raises(qv.QuiverError) as e:
         qv.encode(x, enc=7)
     assert e.value.code == -1
-    codes = torch.zeros((10, 10), dtype=torch.int64, device="cuda")   # 2-bit codes of d = 320: no construction kernel
+    codes = torch.zeros((10, 26), dtype=torch.int64, device="cuda")   # 2-bit codes of d = 800: no construction kernel that wide
     with pytest.raises(qv.QuiverError) as e:
-        qv.build_graph(codes, 320, 8, 16, 1.2, 0, enc=qv.ENC_SQ2)
+        qv.build_graph(codes, 800, 8, 16, 1.2, 0, enc=qv.ENC_SQ2)
     assert e.value.code == -9
     assert qv.code_words(768, qv.ENC_SIGN1) == 12 and qv.code_words(768, qv.ENC_SQ2) == 24 and qv.code_words(768, 9) == 0

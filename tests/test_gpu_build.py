@@ -38,6 +38,9 @@ def _compare(qv, codes, d, R, L, alpha, entry, max_batch=1 << 20):
     (1500, 128, 16, 32, 1.2, 7), (2500, 384, 32, 48, 1.2, 0), (1200, 768, 16, 48, 1.2, 1199),
     (100, 768, 64, 128, 1.2, 0), (600, 128, 64, 128, 1.2, 11), (3000, 100, 8, 16, 1.0, 5),
     (900, 512, 12, 192, 1.5, 450), (300, 1024, 24, 64, 1.2, 3), (40, 128, 64, 64, 1.2, 0),
+    # widths the selection kernels are not compiled for (zero-padded in the workspace), and the widest they take
+    (700, 300, 16, 32, 1.2, 7), (250, 960, 16, 48, 1.2, 3), (800, 40, 8, 16, 1.2, 0), (800, 200, 16, 32, 1.2, 9),
+    (200, 1536, 16, 32, 1.2, 0), (200, 1100, 12, 32, 1.2, 5),
 ])
 def test_build_matches_oracle(qv, n, d, R, L, alpha, entry):
     rng = np.random.default_rng(n + d)
@@ -92,9 +95,9 @@ def test_build_then_search_end_to_end(qv):
 
 
 def test_build_argument_errors(qv):
-    codes = torch.zeros((10, 10), dtype=torch.int64, device="cuda")   # d = 320: width not supported
+    codes = torch.zeros((10, 50), dtype=torch.int64, device="cuda")   # d = 1600: planes wider than the selection kernels take
     with pytest.raises(qv.QuiverError) as e:
-        qv.build_graph(codes, 320, 8, 16, 1.2, 0)
+        qv.build_graph(codes, 1600, 8, 16, 1.2, 0)
     assert e.value.code == -9
     codes = torch.zeros((10, 4), dtype=torch.int64, device="cuda")
     for kw in (dict(R=65), dict(L=193), dict(alpha=0.5), dict(entry=10)):
