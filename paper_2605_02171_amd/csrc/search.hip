@@ -736,7 +736,7 @@ static hipError_t launch_g(const SearchParams& p, int g, hipStream_t stream) {
 #if QV_SEARCH_WIDTH == 0 && QV_SEARCH_ENC == 0
 static int default_lanes_per_row(int nw) {
     if (nw <= 12) return 2;
-    if (nw <= 24) return 4;
+    if (nw <= 32) return 4;   // 2048-d: 1.69 ms with 4 lanes per row against 2.02 with 16 (400k vectors, ef = 64)
     return 16;
 }
 
