@@ -409,8 +409,10 @@ hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_
     switch ((d + 63) / 64) {
 #define QV_ENC_CASE(W, ROWS) case W: hipLaunchKernelGGL((encode_kernel_reg<W, ROWS>), grid_for(ROWS), block, 0, stream, x, n, d, codes, status); break;
         QV_ENC_CASE(1, 8) QV_ENC_CASE(2, 4) QV_ENC_CASE(3, 4) QV_ENC_CASE(4, 4) QV_ENC_CASE(5, 2) QV_ENC_CASE(6, 2)
-        QV_ENC_CASE(8, 1) QV_ENC_CASE(10, 1) QV_ENC_CASE(12, 1) QV_ENC_CASE(15, 1) QV_ENC_CASE(16, 1) QV_ENC_CASE(20, 1)
-        QV_ENC_CASE(24, 1) QV_ENC_CASE(32, 1) QV_ENC_CASE(48, 1) QV_ENC_CASE(64, 1)
+        QV_ENC_CASE(7, 1) QV_ENC_CASE(8, 1) QV_ENC_CASE(9, 1) QV_ENC_CASE(10, 1) QV_ENC_CASE(11, 1) QV_ENC_CASE(12, 1)
+        QV_ENC_CASE(13, 1) QV_ENC_CASE(14, 1) QV_ENC_CASE(15, 1) QV_ENC_CASE(16, 1) QV_ENC_CASE(17, 1) QV_ENC_CASE(18, 1)
+        QV_ENC_CASE(19, 1) QV_ENC_CASE(20, 1) QV_ENC_CASE(21, 1) QV_ENC_CASE(22, 1) QV_ENC_CASE(23, 1) QV_ENC_CASE(24, 1)
+        QV_ENC_CASE(32, 1) QV_ENC_CASE(48, 1) QV_ENC_CASE(64, 1)
 #undef QV_ENC_CASE
         default: hipLaunchKernelGGL(encode_kernel, grid, block, 0, stream, x, n, d, codes, status);
     }

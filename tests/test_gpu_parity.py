@@ -37,7 +37,7 @@ def _special_vectors(d, rng):
     return np.stack(rows)
 
 
-@pytest.mark.parametrize("d", [1, 2, 63, 64, 65, 100, 128, 192, 200, 300, 384, 512, 640, 768, 960, 1000, 1200, 1280, 1536, 3072,
+@pytest.mark.parametrize("d", [1, 2, 63, 64, 65, 100, 128, 192, 200, 300, 384, 448, 512, 640, 768, 832, 960, 1000, 1200, 1280, 1472, 1536, 1600, 3072,
                                4096, 4100])
 def test_encode_bit_exact(qv, d):
     rng = np.random.default_rng(100 + d)
