@@ -444,3 +444,32 @@ def test_search_replays_from_a_captured_graph(qv):
         assert torch.equal(out.cand_ids, eager.cand_ids) and torch.equal(out.cand_dist, eager.cand_dist), rep
         assert torch.equal(out.ids, eager.ids) and torch.equal(out.scores, eager.scores), rep
         assert torch.equal(out.n_expanded, eager.n_expanded), rep
+
+
+def test_searches_on_two_streams_at_once(qv):
+    # the index is read-only and all scratch lives in the caller's workspace: two searches with separate workspaces
+    # may run on different streams at the same time (default stream priority); each must equal its own solo run
+    w = datagen.scaled("C3", n=20_000, nq=4500)
+    x = datagen.make_base(w)
+    adj, entry = graph.build_graph(x, 32, 32, 1.2)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, entry)
+    rng = np.random.default_rng(11)
+    qa = torch.from_numpy(rng.standard_normal((w.nq, w.d)).astype(np.float32)).cuda()
+    qb = torch.from_numpy(rng.standard_normal((1500, w.d)).astype(np.float32)).cuda()
+    solo_a = qv.search(index, qa, 10, 48, trace=True)
+    solo_b = qv.search(index, qb, 5, 100, trace=True)
+    torch.cuda.synchronize()
+    ref = oracle.search(qb.cpu().numpy()[:50], adj, oracle.encode(x, threads=8), x, entry, 5, 100, threads=8)
+    assert (qv.to_numpy_u32(solo_b.cand_ids)[:50] == ref.cand_ids).all()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        with torch.cuda.stream(sa):
+            out_a = qv.search(index, qa, 10, 48, trace=True)
+        with torch.cuda.stream(sb):
+            out_b = qv.search(index, qb, 5, 100, trace=True)
+        sa.synchronize(); sb.synchronize()
+        for got, want in ((out_a, solo_a), (out_b, solo_b)):
+            assert torch.equal(got.cand_ids, want.cand_ids) and torch.equal(got.cand_dist, want.cand_dist), rep
+            assert torch.equal(got.ids, want.ids) and torch.equal(got.scores, want.scores), rep
+            assert torch.equal(got.n_expanded, want.n_expanded), rep
