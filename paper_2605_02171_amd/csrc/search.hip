@@ -441,12 +441,14 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
         wave_sync();  // list[] written by other lanes
         uint64_t mine = KEY_NONE;
         if constexpr (QUAD_REDUCE) {
-            // pass b handles row b*RPP + grp; all loads first, then the arithmetic
+            // pass b handles row b*RPP + grp; all loads first, then the arithmetic.  Lanes beyond the list load
+            // the list's last row instead of being masked off (the line is in flight anyway, no branch, no
+            // zero fill); what they compute is never used.
             uint64_t pv[G][KW], sv[G][KW];
 #pragma unroll
             for (int b = 0; b < G; ++b) {
-                const int ri = b * RPP + grp;
-                if (ri < m) {
+                if (b * RPP < m) {  // wave-uniform
+                    const int ri = min(b * RPP + grp, m - 1);
                     const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
                     if constexpr (BLOCKED) {
                         const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
@@ -472,9 +474,6 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                             sv[b][i] = (PLANES == 2 && w < NW_T) ? row[NW_T + w] : 0ull;
                         }
                     }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < KW; ++i) pv[b][i] = sv[b][i] = 0ull;
                 }
             }
             uint32_t part[G];
