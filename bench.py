@@ -61,6 +61,7 @@ def main() -> int:
     ap.add_argument("--lanes-per-row", type=int, default=0)
     ap.add_argument("--table-format", type=int, default=0)
     ap.add_argument("--visited-mode", type=int, default=0, help="0 default, 1 exact table, 2 cache")
+    ap.add_argument("--rerank-mode", type=int, default=0, help="0 default, 1 a kernel of its own, 2 inside the search kernel")
     ap.add_argument("--gpu-build", action="store_true",
                     help="also build the graph on the GPU (qv_build_graph), time it and search it")
     ap.add_argument("--graph", choices=("host", "gpu"), default="host",
@@ -162,7 +163,7 @@ def main() -> int:
     n_overflow = int((qv.to_numpy_u32(exact.status) & 2 != 0).sum())
     del exact
     # the configuration that is timed (default: visited set as a small cache): results for recall / parity
-    index.set_tuning(args.visited_slots, args.lanes_per_row, args.table_format, args.visited_mode)
+    index.set_tuning(args.visited_slots, args.lanes_per_row, args.table_format, args.visited_mode, args.rerank_mode)
     traced = qv.search(index, qd, k, ef, trace=True, workspace=ws)
     torch.cuda.synchronize()
     n_eval_run = qv.to_numpy_u32(traced.n_dist_evals).astype(np.int64)
@@ -330,7 +331,10 @@ def main() -> int:
         with open(tpath) as f:
             traffic = json.load(f).get("search_kernel_hbm_bytes_per_launch")
 
-    achieved = search_bytes / (search_ms * 1e-3) / 1e9
+    # with Stage 2 inside the search kernel that kernel's bytes are those of both stages
+    fused = index.rerank_fused(ef)
+    kernel_bytes = search_bytes + (rerank_bytes if fused else 0)
+    achieved = kernel_bytes / (search_ms * 1e-3) / 1e9
     line = {
         "metric": "QPS at Recall@10 (ef=%d), 1M x 768 on 1 MI355X" % ef if w.name == "C2" and not args.n
                   else f"QPS at Recall@10 (ef={ef})",
@@ -357,7 +361,8 @@ def main() -> int:
         # `achieved` counts the bytes the algorithm needs; rows that several queries share (the start of every search,
         # hub nodes) are served by L2 / Infinity Cache, so it can exceed what the fabric moved (`traffic`) and even the
         # HBM peak
-        "roofline": {"kernel": "beam_search_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+        "rerank_inside_search_kernel": fused,
+        "roofline": {"kernel": "beam_search_kernel (search + rerank)" if fused else "beam_search_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "traffic_GBps": traffic / (search_ms * 1e-3) / 1e9 if traffic else None},
         "cpu_baseline": cpu,

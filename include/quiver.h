@@ -222,10 +222,23 @@ int qv_index_set_encoding(qv_index* index, int encoding);
  *                    QV_VISITED_EXACT  never forgets an id; when the table is nearly full it stops taking ids
  *                    QV_VISITED_CACHE  a small table in which new ids displace old ones: a forgotten node that
  *                                      comes up again is evaluated again and dropped when it is merged
- *                    Either way status bit 2 of a query says that nodes may have been evaluated more than once. */
+ *                    Either way status bit 2 of a query says that nodes may have been evaluated more than once.
+ *    rerank_mode     where Stage 2 of Sec. 3.3 runs (same scores to the tolerance of the rerank, same order):
+ *                    QV_RERANK_FUSED     inside the search kernel, by the wave that finished the query's Stage 1, so
+ *                                        that its row reads fill the time other waves spend waiting for gathers.
+ *                                        Only for ef <= 128 and vectors in device memory; elsewhere it is ignored.
+ *                    QV_RERANK_SEPARATE  a kernel of its own after the search.
+ *                    0: fused where it applies and a code row is at most 128 bytes long (d <= 512 for the 2-bit
+ *                       codes), where it is the faster form; separate otherwise. */
 #define QV_VISITED_EXACT 1
 #define QV_VISITED_CACHE 2
-int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode);
+#define QV_RERANK_SEPARATE 1
+#define QV_RERANK_FUSED 2
+int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode,
+                        int rerank_mode);
+/* 1 if a search with this beam width runs Stage 2 inside the search kernel as the index is set up now, else 0
+ * (QV_ERR_NULL without an index).  Host only. */
+int qv_index_rerank_fused(const qv_index* index, int ef);
 
 /*
  * Layout of an index's codes (an option of this library, not of the paper; Sec. 4.2 fixes only what the hot data

@@ -23,6 +23,8 @@ LIB_PATH = os.path.join(_HERE, "libquiver_hip.so")
 EMPTY = 0xFFFFFFFF
 VISITED_EXACT = 1
 VISITED_CACHE = 2
+RERANK_SEPARATE = 1
+RERANK_FUSED = 2
 ENC_SM, ENC_SIGN1, ENC_SQ2 = 0, 1, 2
 STATUS_NONFINITE = 1
 STATUS_VISITED_FULL = 2
@@ -71,7 +73,7 @@ _lib.qv_index_load.argtypes = [ctypes.POINTER(_P), ctypes.c_int64, ctypes.c_int,
 _lib.qv_index_free.restype = None
 _lib.qv_index_free.argtypes = [_P]
 _lib.qv_index_set_tuning.restype = ctypes.c_int
-_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+_lib.qv_index_set_tuning.argtypes = [_P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_code_words_enc.restype = ctypes.c_int
 _lib.qv_code_words_enc.argtypes = [ctypes.c_int, ctypes.c_int]
 _lib.qv_encode_enc.restype = ctypes.c_int
@@ -86,6 +88,8 @@ _lib.qv_build_graph_enc.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_i
                                     ctypes.c_double, ctypes.c_uint32, ctypes.c_int64, _P, _P, ctypes.c_size_t, _P]
 _lib.qv_index_set_encoding.restype = ctypes.c_int
 _lib.qv_index_set_encoding.argtypes = [_P, ctypes.c_int]
+_lib.qv_index_rerank_fused.restype = ctypes.c_int
+_lib.qv_index_rerank_fused.argtypes = [_P, ctypes.c_int]
 _lib.qv_code_layout.restype = ctypes.c_int
 _lib.qv_code_layout.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
 _lib.qv_pad_codes.restype = ctypes.c_int
@@ -323,9 +327,13 @@ class Index:
             _check(_lib.qv_index_set_code_layout(h, int(layout[0]), int(layout[1])), "qv_index_set_code_layout")
 
     def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0,
-                   visited_mode: int = 0) -> None:
-        _check(_lib.qv_index_set_tuning(self._h, visited_slots, lanes_per_row, table_format, visited_mode),
+                   visited_mode: int = 0, rerank_mode: int = 0) -> None:
+        _check(_lib.qv_index_set_tuning(self._h, visited_slots, lanes_per_row, table_format, visited_mode, rerank_mode),
                "qv_index_set_tuning")
+
+    def rerank_fused(self, ef: int) -> bool:
+        """qv_index_rerank_fused: does a search with this beam width score its lists inside the search kernel?"""
+        return bool(_lib.qv_index_rerank_fused(self._h, int(ef)))
 
     def set_timer(self, timer: Timer | None) -> None:
         self._timer = timer

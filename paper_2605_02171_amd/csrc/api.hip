@@ -64,6 +64,8 @@ struct qv_index {
     int lanes_per_row;  // <= 0: choose from d
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
     int visited_mode;   // 0: choose from ef; QV_VISITED_EXACT; QV_VISITED_CACHE
+    int rerank_mode;    // 0: choose; QV_RERANK_SEPARATE; QV_RERANK_FUSED
+    bool vecs_on_device;  // false: the float32 vectors live in host memory the device can address
     int encoding;       // QV_ENC_*: what `codes` holds and what the queries are encoded to
     int code_plane_words;  // 64-bit words per bit-plane as stored in `codes`; 0: ceil(d / 64)
     int code_stride;    // 64-bit words between rows of `codes`; 0: dense
@@ -193,23 +195,31 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->encoding = QV_ENC_SM; ix->code_plane_words = 0; ix->code_stride = 0; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->rerank_mode = 0; ix->encoding = QV_ENC_SM; ix->code_plane_words = 0; ix->code_stride = 0; ix->timer = nullptr;
+    // where the cold data lives decides whether Stage 2 may run inside the search kernel (host memory: never)
+    hipPointerAttribute_t attr;
+    ix->vecs_on_device = true;
+    if (hipPointerGetAttributes(&attr, vecs) == hipSuccess) ix->vecs_on_device = attr.type != hipMemoryTypeHost;
+    else (void)hipGetLastError();   // an address the runtime does not know: treat as device memory
     *out = ix;
     return QV_OK;
 }
 
 void qv_index_free(qv_index* index) { delete index; }
 
-int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode) {
+int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode,
+                        int rerank_mode) {
     if (!index) return QV_ERR_NULL;
     if (visited_slots != 0 && (visited_slots < 1024 || visited_slots > 28672)) return QV_ERR_INVALID_ARG;
     if (table_format != 0 && table_format != 32) return QV_ERR_INVALID_ARG;
     if (visited_mode != 0 && visited_mode != QV_VISITED_EXACT && visited_mode != QV_VISITED_CACHE) return QV_ERR_INVALID_ARG;
+    if (rerank_mode != 0 && rerank_mode != QV_RERANK_SEPARATE && rerank_mode != QV_RERANK_FUSED) return QV_ERR_INVALID_ARG;
     if (lanes_per_row > 0 && (lanes_per_row > 16 || (lanes_per_row & (lanes_per_row - 1)))) return QV_ERR_INVALID_ARG;
     index->visited_slots = visited_slots;
     index->lanes_per_row = lanes_per_row;
     index->table_format = table_format;
     index->visited_mode = visited_mode;
+    index->rerank_mode = rerank_mode;
     return QV_OK;
 }
 
@@ -272,6 +282,18 @@ int qv_index_set_code_layout(qv_index* index, int plane_words, int stride) {
     index->code_plane_words = plane_words;
     index->code_stride = stride;
     return QV_OK;
+}
+
+static bool rerank_is_fused(const qv_index* index, int ef, int row_words) {
+    const bool can_fuse = ef <= 128 && index->vecs_on_device;
+    return can_fuse && (index->rerank_mode == QV_RERANK_FUSED || (index->rerank_mode == 0 && row_words * 8 <= 128));
+}
+
+int qv_index_rerank_fused(const qv_index* index, int ef) {
+    if (!index) return QV_ERR_NULL;
+    const int planes = index->encoding == QV_ENC_SIGN1 ? 1 : 2;
+    const int pw = index->code_stride > 0 ? index->code_plane_words : (index->d + 63) / 64;
+    return rerank_is_fused(index, ef, planes * pw) ? 1 : 0;
 }
 
 size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef) {
@@ -341,15 +363,26 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     if (sp.vis_regions == 0 && sp.vis_slots > 8192) {  // 32-bit entries: keep the table within 32 KB of LDS
         qv::plan_visited_table(sp, 8192, false, cache);
     }
+    // Stage 2 inside the search kernel (beams of up to 128 entries over vectors in device memory): by default where a
+    // code row is at most one 128-byte line -- there the search waits on latency and the row reads of finished queries
+    // fill idle memory time (1M x 384: 1.21 -> 1.15 ms per 10,000 queries, 1M x 512: 1.27 -> 1.23) -- and not for wider
+    // rows, where the search already moves lines as fast as the memory system does and the two kernels stream better
+    // one after the other (1M x 768: 1.26 -> 1.32 ms, 1M x 3072: 4.66 -> 4.92).  When fused, the final lists leave the
+    // kernel only if the caller's trace asks for them.
+    const bool fused = rerank_is_fused(index, ef, planes * plane_words);
     // the final lists go straight into the caller's trace buffers when there are any
     sp.cand_ids = trace && trace->cand_ids ? trace->cand_ids : reinterpret_cast<uint32_t*>(ws + L.cand_ids);
     sp.cand_dist = trace && trace->cand_dist ? trace->cand_dist : reinterpret_cast<uint32_t*>(ws + L.cand_dist);
     sp.n_cand = trace && trace->n_cand ? trace->n_cand : reinterpret_cast<uint32_t*>(ws + L.n_cand);
+    if (fused && !(trace && (trace->cand_ids || trace->cand_dist))) sp.cand_ids = sp.cand_dist = nullptr;
+    if (fused && !(trace && trace->n_cand)) sp.n_cand = nullptr;
     sp.n_expanded = trace ? trace->n_expanded : nullptr;
     sp.n_evals = trace ? trace->n_dist_evals : nullptr;
     sp.status = trace ? trace->status : nullptr;
     sp.visit_order = trace ? trace->visit_order : nullptr;
     sp.visit_cap = trace && trace->visit_order ? trace->visit_cap : 0;
+    sp.rr_queries = fused ? queries : nullptr; sp.rr_vecs = fused ? index->vecs : nullptr;
+    sp.rr_d = index->d; sp.rr_k = k; sp.rr_ids = ids; sp.rr_scores = scores;
     sp.order = nullptr;
     if (qv::launch_query_order(sp, reinterpret_cast<uint32_t*>(ws + L.order), stream, &e))
         sp.order = reinterpret_cast<uint32_t*>(ws + L.order);
@@ -359,11 +392,13 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     if (e != hipSuccess) return hip_fail(e, "beam search launch");
     if (ev && (e = hipEventRecord(ev[2], stream)) != hipSuccess) return hip_fail(e, "event record");
 
-    qv::RerankParams rp;
-    rp.queries = queries; rp.vecs = index->vecs; rp.cand_ids = sp.cand_ids; rp.n_cand = sp.n_cand;
-    rp.nq = nq; rp.d = index->d; rp.ef = ef; rp.k = k; rp.ids = ids; rp.scores = scores;
-    e = qv::launch_rerank(rp, stream);
-    if (e != hipSuccess) return hip_fail(e, "rerank launch");
+    if (!fused) {
+        qv::RerankParams rp;
+        rp.queries = queries; rp.vecs = index->vecs; rp.cand_ids = sp.cand_ids; rp.n_cand = sp.n_cand;
+        rp.nq = nq; rp.d = index->d; rp.ef = ef; rp.k = k; rp.ids = ids; rp.scores = scores;
+        e = qv::launch_rerank(rp, stream);
+        if (e != hipSuccess) return hip_fail(e, "rerank launch");
+    }
     if (ev && (e = hipEventRecord(ev[3], stream)) != hipSuccess) return hip_fail(e, "event record");
 
     return QV_OK;

@@ -41,6 +41,14 @@ struct SearchParams {
     uint32_t* status;        // [nq] or null
     uint32_t* visit_order;   // [nq][visit_cap] or null
     int64_t visit_cap;
+    // Stage 2 inside the search kernel (rr_vecs != null; beams of up to 128 entries): the wave that finished a query
+    // scores its final list at once, so that this streaming work fills the time in which other waves wait for their
+    // gathers.  cand_ids / cand_dist / n_cand may then be null.
+    const float* rr_queries;  // [nq][rr_d]
+    const float* rr_vecs;     // [n][rr_d]
+    int rr_d, rr_k;
+    uint32_t* rr_ids;         // [nq][rr_k]
+    float* rr_scores;         // [nq][rr_k]
 };
 
 struct RerankParams {

@@ -369,6 +369,148 @@ __device__ __forceinline__ void merge_new_keys_wide(Pool<P>& pool, uint64_t mine
     pool.size = new_size;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Stage 2 (paper Sec. 3.3) by the wave that just finished Stage 1 of a query: exact cosine between the float32
+// query and every member of the final list, best k by (score descending, id ascending).  Four candidates at a
+// time: their rows are streamed with coalesced 16-byte loads (all loads of the four rows in flight together when the
+// width is known at compile time), dot product and squared norm are accumulated in double per lane, and the eight
+// per-lane sums are reduced together -- each exchange step halves what a lane still carries, so the wave-wide
+// reduction of eight values costs 20 lane exchanges instead of 96.  Scores and ids go to LDS (the merge area, which
+// is free by now), ranks come from counting.
+__device__ __forceinline__ double lane_xor_f64(double v, int mask) { return __shfl_xor(v, mask); }
+
+template <int NW_T, int P>
+__device__ __forceinline__ void rerank_own_list(const SearchParams& p, int64_t q, const Pool<P>& pool, int lane, uint64_t* skeys) {
+    const int d = p.rr_d, nc = pool.size, k = p.rr_k;
+    const float* qf = p.rr_queries + q * (int64_t)d;
+    float* s_score = reinterpret_cast<float*>(skeys);              // [64 * P]
+    uint32_t* s_id = reinterpret_cast<uint32_t*>(s_score + 64 * P);  // [64 * P]
+    const bool vec4 = (d & 3) == 0;
+    const int d4 = d >> 2;
+    constexpr int IT = NW_T > 0 ? (NW_T + 3) / 4 : 2;   // float4 per lane and row when the width is known
+    constexpr int CH = IT < 4 ? IT : 4;
+
+    double qq = 0.0;
+    if (vec4) {
+        const float4* q4 = reinterpret_cast<const float4*>(qf);
+        for (int i = lane; i < d4; i += 64) {
+            const float4 a = q4[i];
+            qq += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+        }
+    } else {
+        for (int i = lane; i < d; i += 64) qq += (double)qf[i] * (double)qf[i];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) qq += lane_xor_f64(qq, off);
+
+    wave_sync();  // the merge area is read as keys no more
+    for (int c0 = 0; c0 < nc; c0 += 4) {
+        uint32_t id[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = min(c0 + j, nc - 1);   // beyond the list: the last member again, result dropped
+            uint32_t v = 0;
+#pragma unroll
+            for (int r = 0; r < P; ++r)
+                if (r == (c >> 6)) v = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(pool.key[r] >> 1), c & 63);
+            id[j] = v;
+        }
+        double acc[8];   // dot0, xx0, dot1, xx1, dot2, xx2, dot3, xx3
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0;
+        if (vec4) {
+            // CH float4 per lane and row at a time: all loads of a chunk (four rows and the query) before its arithmetic
+            const float4* q4 = reinterpret_cast<const float4*>(qf);
+            for (int base = 0; base < d4; base += 64 * CH) {
+                float4 xv[4][CH], qv4[CH];
+#pragma unroll
+                for (int it = 0; it < CH; ++it) {
+                    const int i = min(base + it * 64 + lane, d4 - 1);   // clamped: masked below
+                    qv4[it] = q4[i];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) xv[j][it] = reinterpret_cast<const float4*>(p.rr_vecs + (int64_t)id[j] * d)[i];
+                }
+#pragma unroll
+                for (int it = 0; it < CH; ++it) {
+                    if (base + it * 64 + lane < d4) {
+                        const float4 b = qv4[it];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float4 a = xv[j][it];
+                            acc[2 * j] += (double)a.x * b.x + (double)a.y * b.y + (double)a.z * b.z + (double)a.w * b.w;
+                            acc[2 * j + 1] += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+                        }
+                    }
+                }
+            }
+        } else {
+            for (int i = lane; i < d; i += 64) {
+                const double b = qf[i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const double a = p.rr_vecs[(int64_t)id[j] * d + i];
+                    acc[2 * j] += a * b;
+                    acc[2 * j + 1] += a * a;
+                }
+            }
+        }
+        // eight sums over 64 lanes: halves of the wave keep candidates {0,1} / {2,3}, then quarters one candidate each,
+        // then eighths either its dot product or its squared norm; three plain steps finish inside groups of eight
+        double h4[4], h2[2], v;
+        {
+            const bool up = lane & 32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) h4[j] = (up ? acc[4 + j] : acc[j]) + lane_xor_f64(up ? acc[j] : acc[4 + j], 32);
+        }
+        {
+            const bool up = lane & 16;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) h2[j] = (up ? h4[2 + j] : h4[j]) + lane_xor_f64(up ? h4[j] : h4[2 + j], 16);
+        }
+        {
+            const bool up = lane & 8;
+            v = (up ? h2[1] : h2[0]) + lane_xor_f64(up ? h2[0] : h2[1], 8);
+        }
+        v += lane_xor_f64(v, 4);
+        v += lane_xor_f64(v, 2);
+        v += lane_xor_f64(v, 1);
+        const double other = lane_xor_f64(v, 8);   // lanes 0, 16, 32, 48: v = dot, other = squared norm of candidate lane / 16
+        if ((lane & 15) == 0) {
+            const int j = lane >> 4;
+            if (c0 + j < nc) {
+                float sc = 0.0f;
+                if (qq != 0.0 && other != 0.0) sc = (float)(v / (sqrt(qq) * sqrt(other)));
+                s_score[c0 + j] = sc;
+                s_id[c0 + j] = j == 0 ? id[0] : (j == 1 ? id[1] : (j == 2 ? id[2] : id[3]));
+            }
+        }
+    }
+    wave_sync();
+    // rank by counting: position of candidate t = number of candidates that come before it
+#pragma unroll
+    for (int r = 0; r < P; ++r) {
+        const int t = r * 64 + lane;
+        if (t < nc) {
+            const float st = s_score[t];
+            const uint32_t it = s_id[t];
+            int rank = 0;
+            for (int j = 0; j < nc; ++j) {
+                const float sj = s_score[j];
+                const uint32_t ij = s_id[j];
+                rank += (sj > st || (sj == st && ij < it)) ? 1 : 0;
+            }
+            if (rank < k) {
+                p.rr_ids[q * (int64_t)k + rank] = it;
+                p.rr_scores[q * (int64_t)k + rank] = st;
+            }
+        }
+    }
+    for (int r = nc + lane; r < k; r += 64) {
+        p.rr_ids[q * (int64_t)k + r] = EMPTY_ID;
+        p.rr_scores[q * (int64_t)k + r] = -__builtin_inff();
+    }
+}
+
 template <int ENC, int NW_T, int G, int P, bool NARROW>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
@@ -669,21 +811,26 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     }
 
     // results: sorted list, counters
-    uint32_t* cid = p.cand_ids + q * (int64_t)ef;
-    uint32_t* cds = p.cand_dist + q * (int64_t)ef;
+    if (p.cand_ids) {
+        uint32_t* cid = p.cand_ids + q * (int64_t)ef;
+        uint32_t* cds = p.cand_dist + q * (int64_t)ef;
 #pragma unroll
-    for (int r = 0; r < P; ++r) {
-        int e = r * 64 + lane;
-        if (e < ef) {
-            bool has = pool.key[r] != KEY_NONE;
-            cid[e] = has ? (uint32_t)(pool.key[r] >> 1) : EMPTY_ID;
-            cds[e] = has ? (uint32_t)(pool.key[r] >> 33) : EMPTY_ID;
+        for (int r = 0; r < P; ++r) {
+            int e = r * 64 + lane;
+            if (e < ef) {
+                bool has = pool.key[r] != KEY_NONE;
+                cid[e] = has ? (uint32_t)(pool.key[r] >> 1) : EMPTY_ID;
+                cds[e] = has ? (uint32_t)(pool.key[r] >> 33) : EMPTY_ID;
+            }
         }
     }
     status = (uint32_t)__builtin_amdgcn_readfirstlane((int)status) |
              (__any(status & QV_STATUS_BAD_EDGE_BIT) ? QV_STATUS_BAD_EDGE_BIT : 0u);
+    if constexpr (P <= 2) {
+        if (p.rr_vecs) rerank_own_list<NW_T, P>(p, q, pool, lane, skeys);
+    }
     if (lane == 0) {
-        p.n_cand[q] = (uint32_t)pool.size;
+        if (p.n_cand) p.n_cand[q] = (uint32_t)pool.size;
         if (p.n_expanded) p.n_expanded[q] = n_exp;
         if (p.n_evals) p.n_evals[q] = n_eval;
         if (p.status) p.status[q] = status;

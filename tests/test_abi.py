@@ -146,10 +146,12 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_search(h, fake, 1, 1, 8, fake, fake, fake, 16, None, None) == -6             # too small
     assert lib.qv_search(h, None, 1, 1, 8, fake, fake, fake, 1 << 20, None, None) == -2
     assert lib.qv_search(h, None, 0, 1, 8, None, None, None, 0, None, None) == 0               # empty batch
-    lib.qv_index_set_tuning.argtypes = [P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
-    assert lib.qv_index_set_tuning(h, 512, 0, 0, 0) == -1 and lib.qv_index_set_tuning(h, 0, 3, 0, 0) == -1
-    assert lib.qv_index_set_tuning(h, 0, 0, 16, 0) == -1 and lib.qv_index_set_tuning(h, 8192, 4, 32, 0) == 0
-    assert lib.qv_index_set_tuning(h, 0, 0, 0, 3) == -1 and lib.qv_index_set_tuning(h, 4096, 2, 0, 2) == 0
+    lib.qv_index_set_tuning.argtypes = [P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    assert lib.qv_index_set_tuning(h, 512, 0, 0, 0, 0) == -1 and lib.qv_index_set_tuning(h, 0, 3, 0, 0, 0) == -1
+    assert lib.qv_index_set_tuning(h, 0, 0, 16, 0, 0) == -1 and lib.qv_index_set_tuning(h, 8192, 4, 32, 0, 0) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 3, 0) == -1 and lib.qv_index_set_tuning(h, 4096, 2, 0, 2, 0) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 3) == -1 and lib.qv_index_set_tuning(h, 0, 0, 0, 0, 1) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 2) == 0
     # layout of the index's codes (d = 8: one word per plane, two planes)
     lib.qv_index_set_code_layout.argtypes = [P, ctypes.c_int, ctypes.c_int]
     ok = lib.qv_index_set_code_layout

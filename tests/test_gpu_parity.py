@@ -126,6 +126,15 @@ def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, visited_slots=0, lanes
     cached = qv.search(index, qd, k, ef, trace=True, visit_cap=visit_cap)
     torch.cuda.synchronize()
     _assert_search_equal(qv, ref, cached, exact_counters=False)
+    plain = qv.search(index, qd, k, ef)          # no trace: the lists never leave the kernel when Stage 2 runs inside it
+    torch.cuda.synchronize()
+    assert torch.equal(plain.ids, cached.ids) and torch.equal(plain.scores, cached.scores)
+    # Stage 2 as a kernel of its own and inside the search kernel (the default picks one of them by the row length)
+    for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED):
+        index.set_tuning(0, lanes, table_format, 0, rerank_mode)
+        other = qv.search(index, qd, k, ef, trace=True, visit_cap=visit_cap)
+        torch.cuda.synchronize()
+        _assert_search_equal(qv, ref, other, exact_counters=False)
     index.set_tuning(visited_slots, lanes, table_format, qv.VISITED_EXACT)
     out = qv.search(index, qd, k, ef, trace=True, visit_cap=visit_cap)
     torch.cuda.synchronize()
