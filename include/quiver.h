@@ -133,7 +133,8 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
  * Stage timer: when one is attached, every qv_search on that index records HIP events around its
  * three stages (query encode together with the launch-order pass, the beam search kernel, rerank) on the
  * search's stream.  qv_timer_read waits for the recorded events and returns milliseconds per stage per
- * recorded call.
+ * recorded call.  When the rerank runs inside the search kernel (qv_index_rerank_fused), the second stage holds
+ * both and the third is the gap between two event records.
  */
 typedef struct qv_timer qv_timer;
 int qv_timer_create(qv_timer** out, int max_calls);
