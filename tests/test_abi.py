@@ -152,6 +152,12 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 3, 0) == -1 and lib.qv_index_set_tuning(h, 4096, 2, 0, 2, 0) == 0
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 3) == -1 and lib.qv_index_set_tuning(h, 0, 0, 0, 0, 1) == 0
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 2) == 0
+    # where Stage 2 runs: inside the search kernel for beams of up to 128 over short code rows (d = 8 here), unless told otherwise
+    lib.qv_index_rerank_fused.argtypes = [P, ctypes.c_int]
+    assert lib.qv_index_rerank_fused(h, 64) == 1 and lib.qv_index_rerank_fused(h, 129) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 1) == 0 and lib.qv_index_rerank_fused(h, 64) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 0) == 0 and lib.qv_index_rerank_fused(h, 64) == 1
+    assert lib.qv_index_rerank_fused(None, 64) == -2
     # layout of the index's codes (d = 8: one word per plane, two planes)
     lib.qv_index_set_code_layout.argtypes = [P, ctypes.c_int, ctypes.c_int]
     ok = lib.qv_index_set_code_layout
