@@ -90,6 +90,8 @@ int qv_gather_probe(const uint64_t* codes, int64_t n, int d, const uint32_t* ids
  *           (hipHostMalloc / pinned): the paper's cold store then stays in host RAM and the rerank's ef rows per
  *           query travel over PCIe
  *    entry  node every search starts from, < n
+ *    The call asks the runtime once where `vecs` lives (device or host memory): the rerank runs inside the search
+ *    kernel only over device memory (qv_index_set_tuning).
  *    1 <= R <= QV_MAX_DEGREE, 1 <= n < 2^32 - 1.
  */
 typedef struct qv_index qv_index;
