@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from tests import pyref
+from tests import cases, pyref
 from workloads import datagen, graph
 
 E = oracle.EMPTY
@@ -99,19 +99,44 @@ def test_bad_arguments():
         oracle.build_graph(codes, 64, 4, 8, 1.2, entry=50)
 
 
-def test_hub_cap_keeps_the_nearest_new_candidates():
-    # 400 identical-direction nodes all select the same hub in one batch; the hub may only consider the 192
-    # nearest of them (ties by id), so its re-selected row must come from ids within that set
-    rng = np.random.default_rng(8)
-    d, n = 64, 60 + 400
-    base = rng.standard_normal((60, d)).astype(np.float32)
-    hub = base[0]
-    crowd = (hub[None, :] + 0.01 * rng.standard_normal((400, d))).astype(np.float32)
-    x = np.concatenate([base, crowd])
-    codes = oracle.encode(x)
-    # one giant batch for the crowd: max_batch large, but batches are done/50, so force it by building the
-    # first 60 nodes one by one and then checking the cap logic on a graph where done/50 >= 1 only; instead
-    # exercise the cap directly through a big max_batch and many duplicates of the hub code
-    adj = oracle.build_graph(codes, d, 8, 16, 1.2, entry=0)
-    for row in adj.tolist():
-        assert len([v for v in row if v != E]) <= 8
+def _algorithm_1(cands, dist_to_t, code_of, d, R, alpha):
+    """Algorithm 1 written out with the level-product distance of tests/pyref (independent of the C oracle)."""
+    sel = []
+    for c in sorted(cands, key=lambda v: (dist_to_t[v], v)):
+        if all(dist_to_t[c] <= alpha * pyref.distance_by_levels(code_of[c], code_of[s], d) for s in sel):
+            sel.append(c)
+        if len(sel) == R:
+            break
+    return sel
+
+
+def test_hub_cap_keeps_the_192_nearest_new_candidates():
+    # 196 nodes arrive in one batch and all select the hub (tests/cases.py): 191 "A" nodes at distance 11-12 that
+    # are within 4 of each other, then B1..B5 at distance 16, 20, 24, 28, 32.  The hub may consider the 192
+    # nearest new candidates by (distance, id) = all A's and B1.  Algorithm 1 then keeps the nearest A (every
+    # other A is within 4 of it: 11 > 1.2 * 4), keeps B1, and fills the row from the hub's old neighbours;
+    # B2..B5, which Algorithm 1 would keep as well, must not appear.
+    d, R, L, alpha = 128, 8, 16, 1.2
+    codes, n0, A, B = cases.hub_crowd_codes()
+    n = codes.shape[0]
+    assert n - n0 == 196 > 192
+    adj = oracle.build_graph(codes, d, R, L, alpha, entry=0)
+    rows = _rows_as_sets(adj)
+    before = _rows_as_sets(oracle.build_graph(codes[:n0], d, R, L, alpha, entry=0))
+    for t in range(n0, n):
+        assert 0 in rows[t]                          # the hub is every new node's nearest node: always selected
+    dist = {v: pyref.distance_by_levels(codes[0], codes[v], d) for v in list(before[0]) + A + B}
+    assert sorted(dist[a] for a in A)[0] >= 11 and max(dist[a] for a in A) == 12
+    assert [dist[b] for b in B] == [16, 20, 24, 28, 32]
+    ranked = sorted(A + B, key=lambda v: (dist[v], v))
+    assert ranked[191] == B[0] and ranked[192] == B[1]
+    want = _algorithm_1(list(before[0]) + ranked[:192], dist, codes, d, R, alpha)
+    assert rows[0] == frozenset(want)
+    # what the row must look like, stated directly
+    assert len(rows[0] & set(A)) == 1 and ranked[0] in rows[0]
+    assert B[0] in rows[0] and not (rows[0] & set(B[1:]))
+    assert len(rows[0]) == R and len(rows[0] & before[0]) == R - 2
+    # the case is sharp: one candidate more or one fewer gives another row
+    for cap in (191, 193):
+        other = _algorithm_1(list(before[0]) + ranked[:cap], dist, codes, d, R, alpha)
+        assert frozenset(other) != rows[0]
