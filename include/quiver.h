@@ -43,7 +43,8 @@ extern "C" {
 #define QV_MAX_SCAN_K 64
 
 /* bits of the per-vector / per-query status words */
-#define QV_STATUS_NONFINITE 1u      /* encode: the vector holds Inf/NaN, its code is unspecified          */
+#define QV_STATUS_NONFINITE 1u      /* encode: the vector holds Inf/NaN, its code is unspecified;           */
+                                    /* search: the query holds Inf/NaN and was not searched                 */
 #define QV_STATUS_VISITED_FULL 2u   /* search: the on-chip visited table filled up; results stay exact,     */
                                     /* n_dist_evals may count some nodes more than once                     */
 #define QV_STATUS_BAD_EDGE 4u       /* search: an adjacency entry >= n was skipped                          */
@@ -127,6 +128,11 @@ size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef);
  *              are scratch (concurrent searches need separate workspaces)
  *    trace     NULL or a struct of optional outputs
  *    1 <= k <= ef <= QV_MAX_EF.  nq == 0 is allowed and does nothing.
+ *    Non-finite input (a precondition violation, reported and never silent): a query that holds Inf or NaN is not
+ *    searched -- all k of its ids are QV_EMPTY and its scores -inf, its list is empty (n_cand, n_expanded,
+ *    n_dist_evals 0; cand_ids, cand_dist, visit_order QV_EMPTY) and its trace status is QV_STATUS_NONFINITE; the other
+ *    queries of the batch are unaffected.  A list member whose stored vector holds Inf or NaN scores -inf, i.e. it
+ *    ranks after every finite score (by id among such members).
  */
 int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids, float* scores,
               void* workspace, size_t workspace_bytes, const qv_trace* trace, void* stream);

@@ -26,7 +26,7 @@ int hip_fail(hipError_t e, const char* where) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t qcodes, qcodes_wide, cand_ids, cand_dist, n_cand, order, total;
+    size_t qcodes, qcodes_wide, cand_ids, cand_dist, n_cand, order, qstatus, total;
 };
 
 // widest plane (64-bit words) an index may store for vectors of nw words per plane: half as much again, plus two
@@ -41,6 +41,7 @@ WorkspaceLayout layout(int64_t nq, int d, int ef) {
     L.cand_dist = off; off = align_up(off + (size_t)nq * ef * 4, 256);
     L.n_cand = off;    off = align_up(off + (size_t)nq * 4, 256);
     L.order = off;     off = align_up(off + (size_t)nq * 4, 256);
+    L.qstatus = off;   off = align_up(off + (size_t)nq * 4, 256);
     L.total = off;
     return L;
 }
@@ -332,7 +333,9 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     if (ev && (e = hipEventRecord(ev[0], stream)) != hipSuccess) return hip_fail(e, "event record");
 
     // Stage 1 preamble: the query's own code, then (index stored with wider planes) the same words in that layout
-    e = qv::launch_encode(queries, nq, index->d, index->encoding, qcodes, nullptr, stream);
+    // (a query that holds Inf or NaN is flagged here and not searched: see the kernel)
+    uint32_t* qstatus = reinterpret_cast<uint32_t*>(ws + L.qstatus);
+    e = qv::launch_encode(queries, nq, index->d, index->encoding, qcodes, qstatus, stream);
     if (e != hipSuccess) return hip_fail(e, "query encode launch");
     if (plane_words != nw) {
         uint64_t* wide = reinterpret_cast<uint64_t*>(ws + L.qcodes_wide);
@@ -343,7 +346,7 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
 
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes; sp.encoding = index->encoding;
-    sp.row_stride = row_stride;
+    sp.row_stride = row_stride; sp.qstatus = qstatus;
     sp.n = index->n; sp.nq = nq; sp.nw = plane_words; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
     // Visited set.  Default: a cache of 4096 slots (8 KB of 16-bit tags): with the list and the merge area a
     // query then needs about 10 KB of LDS, so 16 queries fit a compute unit and registers, not LDS, bound the

@@ -32,6 +32,8 @@ struct SearchParams {
     uint32_t vis_region_buckets;  // ... of this many 8-tag buckets each (see plan_visited_table)
     int vis_cache;           // 0: the table never forgets an id (stops taking ids when nearly full); 1: ids displace each other
     const uint32_t* order;   // [nq] launch order: workgroup b runs query order[b]; null: query b
+    const uint32_t* qstatus; // [nq] status words of the query encode, or null: a query flagged QV_STATUS_NONFINITE_BIT is
+                             // not searched (its code is unspecified) and returns an empty list
     // outputs
     uint32_t* cand_ids;      // [nq][ef]
     uint32_t* cand_dist;     // [nq][ef]

@@ -75,6 +75,7 @@ __global__ __launch_bounds__(RR_THREADS) void rerank_kernel(RerankParams p) {
         if (lane == 0) {
             float s = 0.0f;
             if (qq != 0.0 && xx != 0.0) s = (float)(dot / (sqrt(qq) * sqrt(xx)));
+            if (s != s) s = -INFINITY;   // a stored vector with Inf or NaN in it ranks last (ties by id)
             s_score[c] = s;
             s_id[c] = id;
         }

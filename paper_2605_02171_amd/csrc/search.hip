@@ -480,6 +480,7 @@ __device__ __forceinline__ void rerank_own_list(const SearchParams& p, int64_t q
             if (c0 + j < nc) {
                 float sc = 0.0f;
                 if (qq != 0.0 && other != 0.0) sc = (float)(v / (sqrt(qq) * sqrt(other)));
+                if (sc != sc) sc = -__builtin_inff();   // a stored vector with Inf or NaN in it ranks last
                 s_score[c0 + j] = sc;
                 s_id[c0 + j] = j == 0 ? id[0] : (j == 1 ? id[1] : (j == 2 ? id[2] : id[3]));
             }
@@ -517,6 +518,27 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     const int lane = threadIdx.x;
     const int64_t q = p.order ? (int64_t)p.order[blockIdx.x] : (int64_t)blockIdx.x;
     const int NW = NW_T > 0 ? NW_T : p.nw;
+    if (p.qstatus && (p.qstatus[q] & QV_STATUS_NONFINITE_BIT)) {   // wave-uniform
+        // a query with Inf or NaN in it has no code to search with: empty list, no results, the flag in its status
+        for (int e = lane; e < p.ef; e += 64) {
+            if (p.cand_ids) p.cand_ids[q * (int64_t)p.ef + e] = EMPTY_ID;
+            if (p.cand_dist) p.cand_dist[q * (int64_t)p.ef + e] = EMPTY_ID;
+        }
+        if (p.visit_order)
+            for (int64_t i = lane; i < p.visit_cap; i += 64) p.visit_order[q * p.visit_cap + i] = EMPTY_ID;
+        if (p.rr_vecs)
+            for (int r = lane; r < p.rr_k; r += 64) {
+                p.rr_ids[q * (int64_t)p.rr_k + r] = EMPTY_ID;
+                p.rr_scores[q * (int64_t)p.rr_k + r] = -__builtin_inff();
+            }
+        if (lane == 0) {
+            if (p.n_cand) p.n_cand[q] = 0;
+            if (p.n_expanded) p.n_expanded[q] = 0;
+            if (p.n_evals) p.n_evals[q] = 0;
+            if (p.status) p.status[q] = QV_STATUS_NONFINITE_BIT;
+        }
+        return;
+    }
     const uint32_t cap = p.vis_slots;   // slots (32-bit each, or 16-bit when NARROW)
     const uint32_t vis_regions = p.vis_regions, vis_B = p.vis_region_buckets;
     const uint32_t vis_used = NARROW ? vis_regions * vis_B * 8 : cap;

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import oracle
-from tests import util
+from tests import cases, util
 from workloads import datagen
 
 pytestmark = pytest.mark.gpu
@@ -68,6 +68,15 @@ def test_build_hub_takes_only_the_nearest_new_candidates(qv):
     crowd = (base[0][None, :] + 0.02 * rng.standard_normal((4_000, d))).astype(np.float32)
     codes = oracle.encode(np.concatenate([base, crowd]), threads=8)
     _compare(qv, codes, d, 8, 16, 1.2, 0)
+
+
+def test_build_hub_cap_boundary_case(qv):
+    # the hand-crafted case of the CPU pin (tests/cases.py): 196 nodes select the hub in one batch, candidate 192 by
+    # (distance, id) must be considered and candidate 193 must not
+    codes, n0, A, B = cases.hub_crowd_codes()
+    got = _compare(qv, codes, 128, 8, 16, 1.2, 0)
+    row = set(int(v) for v in got[0] if v != E)
+    assert B[0] in row and not (row & set(B[1:])) and len(row & set(A)) == 1
 
 
 def test_build_then_search_end_to_end(qv):

@@ -482,3 +482,83 @@ def test_searches_on_two_streams_at_once(qv):
             assert torch.equal(got.cand_ids, want.cand_ids) and torch.equal(got.cand_dist, want.cand_dist), rep
             assert torch.equal(got.ids, want.ids) and torch.equal(got.scores, want.scores), rep
             assert torch.equal(got.n_expanded, want.n_expanded), rep
+
+
+@pytest.mark.parametrize("d,ef", [(128, 64), (768, 32), (100, 200)])
+def test_search_reports_non_finite_queries_and_leaves_the_rest_exact(qv, d, ef):
+    # queries with NaN, +Inf and -Inf mixed into a batch: each of them comes back empty and flagged, in both forms of
+    # Stage 2; every other query equals the oracle's result on the finite queries alone (the oracle rejects the others)
+    rng = np.random.default_rng(d + ef)
+    n, nq, k = 4000, 41, 10
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    adj = datagen.random_regular_graph(n, 32, seed=d, fill=0.9)
+    bad = {0: np.nan, 7: np.inf, 8: -np.inf, 23: np.nan, nq - 1: np.inf}
+    for i, v in bad.items():
+        q[i, (i * 13) % d] = v
+    q[23, :] = np.nan
+    good = np.array([i for i in range(nq) if i not in bad])
+    codes = oracle.encode(x, threads=8)
+    with pytest.raises(oracle.OracleError):
+        oracle.search(q[:1], adj, codes, x, 5, k, ef)
+    ref = oracle.search(q[good], adj, codes, x, 5, k, ef, visit_cap=300, threads=8)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, 5)
+    qd = torch.from_numpy(q).cuda()
+    for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED, 0):
+        for visited_mode in (qv.VISITED_EXACT, qv.VISITED_CACHE):
+            index.set_tuning(0, 0, 0, visited_mode, rerank_mode)
+            for trace in (True, False):
+                out = qv.search(index, qd, k, ef, trace=trace, visit_cap=300)
+                torch.cuda.synchronize()
+                ids, scores = qv.to_numpy_u32(out.ids), out.scores.cpu().numpy()
+                for i in bad:
+                    assert (ids[i] == E).all() and np.isneginf(scores[i]).all(), (i, rerank_mode)
+                util.assert_topk_matches(ids[good], scores[good], ref.ids, ref.scores)
+                if not trace:
+                    continue
+                st = qv.to_numpy_u32(out.status)
+                assert (st[list(bad)] == qv.STATUS_NONFINITE).all() and (st[good] & qv.STATUS_NONFINITE == 0).all()
+                for name in ("cand_ids", "cand_dist", "visit_order"):
+                    got = qv.to_numpy_u32(getattr(out, name))
+                    assert (got[list(bad)] == E).all(), name
+                    assert (got[good] == getattr(ref, name)).all(), name
+                for name in ("n_cand", "n_expanded", "n_dist_evals"):
+                    assert (qv.to_numpy_u32(getattr(out, name))[list(bad)] == 0).all(), name
+                assert (qv.to_numpy_u32(out.n_cand)[good] == ref.n_cand).all()
+                assert (qv.to_numpy_u32(out.n_expanded)[good] == ref.n_expanded).all()
+
+
+def test_rerank_puts_non_finite_stored_vectors_last(qv):
+    # an index whose float32 rows hold Inf / NaN (their codes come from clean data): those list members score -inf
+    # and follow every finite score, ordered by id, in both forms of Stage 2
+    rng = np.random.default_rng(5)
+    n, d, nq, ef = 300, 128, 9, 300
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((nq, d)).astype(np.float32)
+    adj = np.stack([(np.arange(n) + s) % n for s in (1, 2, 5, 11, 31, 67)], axis=1).astype(np.uint32)
+    codes = qv.from_numpy_u64(oracle.encode(x))
+    dirty = x.copy()
+    dirty[17, 3], dirty[200, 0], dirty[5, 127] = np.nan, np.inf, -np.inf
+    xd = torch.from_numpy(dirty).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), codes, xd, 0)
+    ref = oracle.search(q, adj, oracle.encode(x), x, 0, n, ef)
+    for ef_run, mode in ((ef, qv.RERANK_SEPARATE), (128, qv.RERANK_FUSED), (128, qv.RERANK_SEPARATE)):
+        index.set_tuning(0, 0, 0, qv.VISITED_EXACT, mode)
+        k = ef_run if ef_run < n else n
+        out = qv.search(index, torch.from_numpy(q).cuda(), k, ef_run, trace=True)
+        torch.cuda.synchronize()
+        ids, scores, cand = qv.to_numpy_u32(out.ids), out.scores.cpu().numpy(), qv.to_numpy_u32(out.cand_ids)
+        for i in range(nq):
+            members = set(cand[i][cand[i] != E].tolist())
+            tail = sorted(members & {5, 17, 200})
+            got_tail = ids[i][np.isneginf(scores[i]) & (ids[i] != E)].tolist()
+            assert got_tail == tail, (i, mode)
+            if tail:
+                first = int(np.flatnonzero(np.isneginf(scores[i]))[0])
+                assert np.isfinite(scores[i][:first]).all() and (np.diff(scores[i][:first]) <= 0).all()
+        if ef_run == ef:     # the whole graph is in the list: the finite part is the oracle's ranking without the three rows
+            keep = ~np.isin(ref.ids, [5, 17, 200])
+            want_ids = np.stack([r[m] for r, m in zip(ref.ids, keep)])
+            want_scores = np.stack([r[m] for r, m in zip(ref.scores, keep)])
+            util.assert_topk_matches(ids[:, :n - 3], scores[:, :n - 3], want_ids, want_scores)
