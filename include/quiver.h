@@ -36,6 +36,7 @@ extern "C" {
 #define QV_ERR_HIP (-7)         /* a HIP runtime call failed (see qv_last_hip_error)   */
 #define QV_ERR_NOMEM (-8)       /* host allocation failed                              */
 #define QV_ERR_UNSUPPORTED (-9) /* the shape is outside what this entry point handles */
+#define QV_ERR_SCRATCH_LIMIT (-10) /* qv_search_static: the batch needs more than QV_STATIC_SCRATCH_BYTES */
 
 #define QV_MAX_DIM 65536
 #define QV_MAX_EF 1024
@@ -136,6 +137,24 @@ size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef);
  */
 int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids, float* scores,
               void* workspace, size_t workspace_bytes, const qv_trace* trace, void* stream);
+
+/*
+ * qv_search for callers that cannot allocate device memory or hand over a workspace: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * qv_search, but the scratch memory is a buffer of QV_STATIC_SCRATCH_BYTES that is part of the library's device code
+ * (one per GPU, held until the process ends); the call allocates and frees nothing.
+ *    - A batch whose qv_search_workspace_bytes(nq, d, k, ef) exceeds QV_STATIC_SCRATCH_BYTES is refused with
+ *      QV_ERR_SCRATCH_LIMIT before anything is launched (16 MiB hold 10,000 queries of 768 dimensions at ef = 64, or
+ *      1,700 at ef = 1024); split larger batches or use qv_search.
+ *    - All calls on one GPU share that GPU's buffer: calls that overlap in time on the same GPU (two streams, two
+ *      threads) race on it and must not be made; calls on one stream, or ordered by events, are fine.
+ *    - The buffer keeps the previous call's contents; every part a call reads it has written first, so nothing
+ *      needs clearing between calls.
+ *    - More than 64 GPUs in one process: QV_ERR_UNSUPPORTED for device numbers from 64 on.
+ */
+#define QV_STATIC_SCRATCH_BYTES (16u << 20)
+int qv_search_static(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids,
+                     float* scores, const qv_trace* trace, void* stream);
 
 /*
  * Stage timer: when one is attached, every qv_search on that index records HIP events around its

@@ -30,6 +30,7 @@ STATUS_NONFINITE = 1
 STATUS_VISITED_FULL = 2
 STATUS_BAD_EDGE = 4
 MAX_EF = 1024
+STATIC_SCRATCH_BYTES = 16 << 20
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -101,6 +102,8 @@ _lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.
 _lib.qv_search.restype = ctypes.c_int
 _lib.qv_search.argtypes = [_P, _P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, _P, ctypes.c_size_t,
                            ctypes.POINTER(_Trace), _P]
+_lib.qv_search_static.restype = ctypes.c_int
+_lib.qv_search_static.argtypes = [_P, _P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, _P, _P, ctypes.POINTER(_Trace), _P]
 _lib.qv_timer_create.restype = ctypes.c_int
 _lib.qv_timer_create.argtypes = [ctypes.POINTER(_P), ctypes.c_int]
 _lib.qv_timer_free.restype = None
@@ -392,4 +395,22 @@ def search(index: Index, queries: torch.Tensor, k: int, ef: int, trace: bool = F
                         workspace.numel() if workspace is not None else 0,
                         ctypes.byref(tr) if tr is not None else None, _stream())
     _check(rc, "qv_search")
+    return out
+
+
+def search_static(index: Index, queries: torch.Tensor, k: int, ef: int, out: SearchOutput) -> SearchOutput:
+    """qv_search_static: qv_search on the library's built-in scratch buffer.  Every output tensor comes from the
+    caller (``out``: ids and scores, plus whichever trace tensors are wanted), so the call allocates nothing."""
+    queries = _dev(queries, torch.float32, "queries")
+    if queries.dim() != 2 or queries.shape[1] != index.d:
+        raise ValueError("queries must be [nq, d]")
+    tr = None
+    if out.cand_ids is not None or out.n_expanded is not None or out.visit_order is not None:
+        ptr = lambda t: t.data_ptr() if t is not None else None
+        tr = _Trace(ptr(out.cand_ids), ptr(out.cand_dist), ptr(out.n_cand), ptr(out.n_expanded),
+                    ptr(out.n_dist_evals), ptr(out.visit_order),
+                    out.visit_order.shape[1] if out.visit_order is not None else 0, ptr(out.status))
+    rc = _lib.qv_search_static(index._h, queries.data_ptr(), queries.shape[0], int(k), int(ef), out.ids.data_ptr(),
+                               out.scores.data_ptr(), ctypes.byref(tr) if tr is not None else None, _stream())
+    _check(rc, "qv_search_static")
     return out

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "../../include/quiver.h"
@@ -302,6 +303,48 @@ size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef) {
     return layout(nq > 0 ? nq : 1, d, ef).total;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Scratch of qv_search_static: one array per GPU, part of the loaded code object, never allocated or freed.  In host
+// code its name is only a handle for hipGetSymbolAddress; the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[QV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device; QV_OK or an error
+int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return QV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return QV_OK;
+}
+}  // namespace
+
+int qv_search_static(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids,
+                     float* scores, const qv_trace* trace, void* stream) {
+    if (!index) return QV_ERR_NULL;
+    if (nq < 0 || nq > 0x7FFFFFFFll || k < 1) return QV_ERR_INVALID_ARG;
+    if (ef < 1 || ef > QV_MAX_EF) return QV_ERR_EF_RANGE;
+    if (k > ef) return QV_ERR_EF_LT_K;
+    if (nq == 0) return QV_OK;
+    if (layout(nq, index->d, ef).total > (size_t)QV_STATIC_SCRATCH_BYTES) return QV_ERR_SCRATCH_LIMIT;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != QV_OK) return rc;
+    return qv_search(index, queries, nq, k, ef, ids, scores, ws, QV_STATIC_SCRATCH_BYTES, trace, stream);
+}
+
 int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, int ef, uint32_t* ids, float* scores,
               void* workspace, size_t workspace_bytes, const qv_trace* trace, void* stream_) {
     if (!index) return QV_ERR_NULL;
@@ -465,6 +508,7 @@ const char* qv_strerror(int code) {
         case QV_ERR_HIP: return "HIP runtime error";
         case QV_ERR_NOMEM: return "host allocation failed";
         case QV_ERR_UNSUPPORTED: return "shape not supported by this entry point";
+        case QV_ERR_SCRATCH_LIMIT: return "the batch needs more scratch than the library's built-in buffer holds (QV_STATIC_SCRATCH_BYTES)";
         default: return "unknown error code";
     }
 }
