@@ -9,6 +9,7 @@ goes to stderr.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -24,6 +25,21 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
 def log(msg: str) -> None:
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def kernel_source_digest() -> str:
+    """sha256 over the sources the search kernel is compiled from: a counter file taken on other code is stale."""
+    h = hashlib.sha256()
+    for name in ("search.hip", "kernels.h"):
+        with open(os.path.join(ROOT, "paper_2605_02171_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def mean_lines_per_row(row_bytes: int, stride_bytes: int) -> float:
+    """128-byte lines a code row touches on average when rows start at multiples of stride_bytes."""
+    starts = {(i * stride_bytes) % 128 for i in range(128)}
+    return float(np.mean([(s + row_bytes + 127) // 128 for s in starts]))
 
 
 def ground_truth(xd, qd, k, metric):
@@ -71,10 +87,12 @@ def main() -> int:
     ap.add_argument("--encoding", choices=("sm", "sign1", "sq2"), default="sm",
                     help="sm: the method; sign1 / sq2: the paper's ablation encodings (graph built on the GPU in that "
                          "encoding's own distance, so --graph gpu is implied and there is no CPU leg)")
-    ap.add_argument("--index-layout", choices=("dense", "recommended"), default="dense",
+    ap.add_argument("--index-layout", choices=("dense", "recommended", "split"), default="dense",
                     help="recommended: the index's code rows in the layout qv_code_layout names (planes padded to a "
                          "compiled kernel width, rows aligned to 128-byte lines); differs from dense rows only at "
-                         "some widths, e.g. 384-d and 960-d")
+                         "some widths, e.g. 384-d and 960-d.  split: sign plane first, the rest of the magnitude "
+                         "plane in a second array that is read only for neighbours the sign-plane bound lets through "
+                         "(768-d, 1024-d, 1536-d)")
     ap.add_argument("--cold-host", action="store_true",
                     help="keep the float32 vectors in pinned host memory (rerank reads them over PCIe)")
     ap.add_argument("--no-scan", action="store_true", help="skip the brute-force code scan / overlap probe")
@@ -146,9 +164,12 @@ def main() -> int:
         x_cold.copy_(torch.from_numpy(x))
     dense_layout = ((w.d + 63) // 64, qv.code_words(w.d, enc))
     layout = qv.code_layout(w.d, enc) if args.index_layout == "recommended" else dense_layout
+    split = qv.split_codes(codes, w.d) if args.index_layout == "split" else None
     index_codes = qv.pad_codes(codes, w.d, layout, enc=enc) if layout != dense_layout else codes
     index = qv.Index(adjd, index_codes, x_cold if args.cold_host else xd, entry, enc=enc,
                      layout=layout if layout != dense_layout else None)
+    if split is not None:
+        index.set_split_codes(split)
     ws = torch.empty((qv.search_workspace_bytes(w.nq, w.d, k, ef),), dtype=torch.uint8, device="cuda")
 
     # Counters for the algorithmic-byte model: one traced pass with the visited set that never forgets, which
@@ -202,7 +223,7 @@ def main() -> int:
 
     # ceiling of the memory system for the search kernel's gather pattern: as many random code rows as the
     # batch evaluates, no arithmetic
-    gather_gbps = None
+    gather_gbps = gather_line_gbps = None
     n_rows = int(n_eval.sum()) // 64 * 64
     if n_rows >= 64 and enc == qv.ENC_SM:      # the probe reads rows of two planes
         rid = torch.randint(0, w.n, (n_rows,), device="cuda", dtype=torch.int32)
@@ -214,8 +235,10 @@ def main() -> int:
             qv.gather_probe(codes, w.d, rid)
         g1.record()
         torch.cuda.synchronize()
-        gather_gbps = n_rows * (code_b + 4) / (g0.elapsed_time(g1) / 3 * 1e-3) / 1e9
-        log(f"random code-row gather ceiling: {gather_gbps:.0f} GB/s")
+        probe_s = g0.elapsed_time(g1) / 3 * 1e-3
+        gather_gbps = n_rows * (code_b + 4) / probe_s / 1e9
+        gather_line_gbps = n_rows * mean_lines_per_row(code_b, code_b) * 128 / probe_s / 1e9
+        log(f"random code-row gather ceiling: {gather_gbps:.0f} GB/s of rows, {gather_line_gbps:.0f} GB/s of 128-byte lines")
         del rid
 
     if args.calib_copy:
@@ -325,16 +348,36 @@ def main() -> int:
                "recall_at_10": orecall}
         log(f"oracle: {n1 / t_1t:.0f} QPS on 1 thread ({n1} queries), {ns / t_cpu:.0f} QPS on {threads} threads, recall {orecall:.4f}, parity with GPU: {parity}")
 
-    traffic = None
+    # counter-measured traffic of the search kernel for this workload, from the committed rocprofv3 summary of this
+    # same command; a file taken on other kernel sources is ignored and reported as stale
+    traffic = l2_hit = traffic_commit = None
+    traffic_stale = False
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}_ef{ef}.json")
-    if os.path.exists(tpath) and not args.n and not args.nq and index_codes is codes:
+    default_run = not (args.n or args.nq or args.visited_slots or args.lanes_per_row or args.table_format or
+                       args.visited_mode or args.rerank_mode or args.cold_host) and args.graph == "host" and enc == qv.ENC_SM
+    if split is not None:
+        tpath = tpath.replace(".json", "_split.json")
+    if os.path.exists(tpath) and default_run and index_codes is codes:
         with open(tpath) as f:
-            traffic = json.load(f).get("search_kernel_hbm_bytes_per_launch")
+            tj = json.load(f)
+        if tj.get("kernel_source_sha256") == kernel_source_digest():
+            traffic = tj.get("search_kernel_hbm_bytes_per_launch")
+            l2_hit = tj.get("l2_hit_rate")
+            traffic_commit = tj.get("commit")
+        else:
+            traffic_stale = True
+            log(f"{os.path.basename(tpath)} was taken on other kernel sources: ignored")
 
     # with Stage 2 inside the search kernel that kernel's bytes are those of both stages
     fused = index.rerank_fused(ef)
     kernel_bytes = search_bytes + (rerank_bytes if fused else 0)
-    achieved = kernel_bytes / (search_ms * 1e-3) / 1e9
+    algorithmic_gbps = kernel_bytes / (search_ms * 1e-3) / 1e9
+    traffic_gbps = traffic / (search_ms * 1e-3) / 1e9 if traffic else None
+    # The fraction of the HBM roofline is taken from the bytes the fabric moved (counters) when a current counter file
+    # exists: rows that several queries share (the start of every search, hub nodes) are served by L2, so the bytes the
+    # algorithm asks for can exceed both what moved and what HBM could move.  Without counters the algorithmic
+    # figure is all there is, and `basis` says so.
+    achieved = traffic_gbps if traffic_gbps else algorithmic_gbps
     line = {
         "metric": "QPS at Recall@10 (ef=%d), 1M x 768 on 1 MI355X" % ef if w.name == "C2" and not args.n
                   else f"QPS at Recall@10 (ef={ef})",
@@ -353,18 +396,23 @@ def main() -> int:
                                        "rerank": rerank_bytes},
         "whole_path_GBps": (encq_bytes + search_bytes + rerank_bytes) / (ms_per_step * 1e-3) / 1e9,
         "encode_base": {"ms": enc_ms, "GBps": enc_bytes / enc_ms / 1e6},
-        "index_code_layout": {"plane_words": layout[0], "row_stride_words": layout[1]}, "graph_build_s": t_graph, "graph_from": args.graph, "encoding": args.encoding,
+        "index_code_layout": {"plane_words": layout[0], "row_stride_words": layout[1], "split": split is not None}, "graph_build_s": t_graph, "graph_from": args.graph, "encoding": args.encoding,
         "random_row_gather_ceiling_GBps": gather_gbps,
         "search_bytes_line_granular": int(4 * w.R * n_exp.sum() + (2 * 128 if code_b % 128 else code_b) * n_eval.sum())
         if code_b <= 256 else None,
         "parity_with_oracle_on_sample": parity,
-        # `achieved` counts the bytes the algorithm needs; rows that several queries share (the start of every search,
-        # hub nodes) are served by L2 / Infinity Cache, so it can exceed what the fabric moved (`traffic`) and even the
-        # HBM peak
         "rerank_inside_search_kernel": fused,
-        "roofline": {"kernel": "beam_search_kernel (search + rerank)" if fused else "beam_search_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "traffic_GBps": traffic / (search_ms * 1e-3) / 1e9 if traffic else None},
+        "random_line_gather_ceiling_GBps": gather_line_gbps,
+        "roofline": {"kernel": "beam_search_kernel (search + rerank)" if fused else "beam_search_kernel", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "basis": "counter traffic (L2-to-fabric bytes) / kernel time" if traffic_gbps
+                              else "algorithmic bytes / kernel time (no current counter file for this run)",
+                     "traffic": traffic, "traffic_GBps": traffic_gbps, "traffic_commit": traffic_commit,
+                     "traffic_file_stale": traffic_stale,
+                     "algorithmic_bytes": kernel_bytes, "algorithmic_GBps": algorithmic_gbps,
+                     "algorithmic_frac": algorithmic_gbps / HBM_PEAK_GBPS, "l2_hit_rate": l2_hit,
+                     "line_rate_frac_of_probe": traffic_gbps / gather_line_gbps if traffic_gbps and gather_line_gbps else None,
+                     "kernel_ms": search_ms},
         "cpu_baseline": cpu,
         "bq_scan": scan,
         "gpu_graph_build": gpu_build,

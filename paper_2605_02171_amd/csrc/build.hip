@@ -9,12 +9,16 @@
 // The paper's own construction is lock-based and concurrent (Sec. 4.1) and has no single defined
 // result; this reading is a function of its inputs, so it can be checked bit for bit.
 //
-// Per batch: beam_search_kernel -> forward_select_kernel (one wave per new node) -> radix sort of the
-// (target, source) pairs (hipCUB) -> reverse_kernel (one wave per target).  Algorithm 1 runs with one
-// lane per already selected neighbour: the candidate's code is wave-uniform (scalar loads), every lane
-// keeps "its" selected code in registers and computes one distance, a ballot decides.
+// Per batch: beam_search_kernel -> forward_select_kernel (one wave per new node; every selected edge (target,
+// source) also counts itself in at its target and learns its rank there) -> reserve_segments_kernel (the edge of
+// rank 0 reserves a segment of the source array for its target) -> scatter_sources_kernel (every edge puts its
+// source at segment start + rank) -> reverse_kernel (one wave per target, started by the edge of rank 0).
+// Grouping the edges by target this way takes three atomics per edge and no sort; the order of the segments and
+// inside them depends on the order of the atomics, the result does not (the reverse step ranks its candidates
+// by (distance, id) itself).  Algorithm 1 runs with one lane per already selected neighbour: the candidate's
+// code is wave-uniform (scalar loads), every lane keeps "its" selected code in registers and computes one
+// distance, a ballot decides.
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
 #include <stdint.h>
 
 #include "kernels.h"
@@ -129,7 +133,13 @@ struct BuildParams {
     const uint32_t* cand_ids;   // [bs][L]
     const uint32_t* cand_dist;  // [bs][L]
     const uint32_t* n_cand;     // [bs]
-    uint64_t* pairs;            // [bs*R] (target << 32 | source), B_NONE where unused
+    // in-edges of the batch, grouped by target (edge e = i * R + j is the j-th edge selected by batch node i)
+    uint32_t* edge_target;      // [bs*R] target of edge e, EMPTY_ID where node i selected fewer than j + 1 edges
+    uint32_t* edge_rank;        // [bs*R] how many edges had counted themselves in at the same target before e
+    uint32_t* tgt_count;        // [n]    edges of this batch per target; 0 outside the reverse step
+    uint32_t* tgt_start;        // [n]    where the target's sources start in `sources`
+    uint32_t* sources;          // [bs*R] sources, one segment per target
+    uint32_t* cursor;           // [1]    words of `sources` reserved so far; 0 between batches
 };
 
 template <int ENC, int NW_T>
@@ -172,22 +182,42 @@ __global__ __launch_bounds__(64) void forward_select_kernel(BuildParams p) {
     if (lane < p.R) {
         const uint32_t s = lane < ns ? sel[lane] : EMPTY_ID;
         p.adj[(int64_t)t * p.R + lane] = s;
-        p.pairs[i * p.R + lane] = lane < ns ? (((uint64_t)s << 32) | t) : B_NONE;
+        p.edge_target[i * p.R + lane] = s;
+        if (lane < ns) p.edge_rank[i * p.R + lane] = atomicAdd(p.tgt_count + s, 1u);
     }
 }
 
+// one thread per edge: the first edge that reached a target reserves room for all of that target's sources
+__global__ __launch_bounds__(256) void reserve_segments_kernel(BuildParams p, int64_t n_edges) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n_edges) return;
+    const uint32_t b = p.edge_target[e];
+    if (b == EMPTY_ID || p.edge_rank[e] != 0) return;
+    p.tgt_start[b] = atomicAdd(p.cursor, p.tgt_count[b]);
+}
+
+// one thread per edge: the source (batch node e / R) goes to its place in the target's segment
+__global__ __launch_bounds__(256) void scatter_sources_kernel(BuildParams p, int64_t n_edges) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n_edges) return;
+    if (e == 0) *p.cursor = 0;                           // every segment is reserved by now; the next batch starts at 0
+    const uint32_t b = p.edge_target[e];
+    if (b == EMPTY_ID) return;
+    p.sources[p.tgt_start[b] + p.edge_rank[e]] = (uint32_t)(p.done + e / p.R);
+}
+
 template <int ENC, int NW_T>
-__global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64_t* __restrict__ sorted,
-                                                     int64_t n_pairs) {
+__global__ __launch_bounds__(64) void reverse_kernel(BuildParams p) {
     __shared__ uint64_t buf[BUF];
     __shared__ uint32_t sel[64];
     __shared__ uint32_t rowcopy[64];
     const int lane = threadIdx.x;
-    const int64_t p0 = blockIdx.x;
-    const uint64_t first = sorted[p0];
-    if (first == B_NONE) return;
-    const uint32_t b = (uint32_t)(first >> 32);
-    if (p0 > 0 && (uint32_t)(sorted[p0 - 1] >> 32) == b) return;  // not the start of b's run
+    const int64_t e0 = blockIdx.x;
+    const uint32_t b = p.edge_target[e0];
+    if (b == EMPTY_ID || p.edge_rank[e0] != 0) return;   // only the edge of rank 0 works on its target
+    const int64_t n_src = p.tgt_count[b];
+    const uint32_t* src = p.sources + p.tgt_start[b];
+    if (lane == 0) p.tgt_count[b] = 0;                   // left as the next batch expects it
 
     const uint32_t v = lane < p.R ? p.adj[(int64_t)b * p.R + lane] : EMPTY_ID;
     rowcopy[lane] = v;
@@ -197,10 +227,9 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
     bsync();
 
     int cnt = 0;  // new candidates in buf[0..cnt)
-    for (int64_t q = p0;; q += 64) {
-        const uint64_t k = q + lane < n_pairs ? sorted[q + lane] : B_NONE;
-        const bool in_run = k != B_NONE && (uint32_t)(k >> 32) == b;
-        const uint32_t t = (uint32_t)k;
+    for (int64_t q = 0; q < n_src; q += 64) {
+        const bool in_run = q + lane < n_src;
+        const uint32_t t = in_run ? src[q + lane] : EMPTY_ID;
         bool ok = in_run && t != b;
         for (int j = 0; j < p.R; ++j) ok &= rowcopy[j] != t;
         const uint32_t dt = ok ? dist_uniform_vs_row<ENC, NW_T>(cb, p.codes, t) : 0u;
@@ -215,7 +244,6 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
         if (ok) buf[cnt + __popcll(om & ((1ull << lane) - 1ull))] = ((uint64_t)dt << 32) | t;
         cnt += m;
         bsync();
-        if (__ballot(in_run) != ~0ull) break;  // the run ended inside this chunk
     }
     if (cnt > MAX_NEW) {
         for (int e = cnt + lane; e < BUF; e += 64) buf[e] = B_NONE;
@@ -224,10 +252,16 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
         cnt = MAX_NEW;
     }
     if (cnt == 0) return;
-    if (deg + cnt <= p.R) {  // room for all: fill the free slots
+    if (deg + cnt <= p.R) {  // room for all: fill the free slots, nearest first (so that the row does not depend on
+                             // the order in which the sources arrived); cnt <= 64, usually 1 to 3: rank by counting
+        const uint64_t key = lane < cnt ? buf[lane] : B_NONE;
+        int rank = 0;
+        for (int j = 0; j < cnt; ++j) rank += buf[j] < key ? 1 : 0;
+        if (lane < cnt) buf[64 + rank] = key;
+        bsync();
         const bool free_slot = lane < p.R && v == EMPTY_ID;
         const int r = __popcll(__ballot(free_slot) & ((1ull << lane) - 1ull));
-        if (free_slot && r < cnt) p.adj[(int64_t)b * p.R + lane] = (uint32_t)buf[r];
+        if (free_slot && r < cnt) p.adj[(int64_t)b * p.R + lane] = (uint32_t)buf[64 + r];
         return;
     }
     // re-select from (old row U new candidates)
@@ -243,16 +277,14 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p, const uint64
     if (lane < p.R) p.adj[(int64_t)b * p.R + lane] = lane < ns ? sel[lane] : EMPTY_ID;
 }
 
-__global__ void fill_empty_kernel(uint32_t* __restrict__ adj, int64_t words) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (int64_t)gridDim.x * blockDim.x)
-        adj[i] = EMPTY_ID;
-}
-
-size_t build_sort_temp_bytes(int64_t max_pairs) {
-    size_t bytes = 0;
-    uint64_t* none = nullptr;
-    (void)hipcub::DeviceRadixSort::SortKeys(nullptr, bytes, none, none, (int)max_pairs, 0, 64, (hipStream_t)0);
-    return bytes;
+// start of a construction: every adjacency slot empty, no edges counted at any target (a kernel, not memset nodes:
+// the whole call may be captured into a graph)
+__global__ void fill_empty_kernel(uint32_t* __restrict__ adj, int64_t words, uint32_t* __restrict__ tgt_count, int64_t n,
+                                  uint32_t* __restrict__ cursor) {
+    const int64_t at = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = at; i < words; i += step) adj[i] = EMPTY_ID;
+    for (int64_t i = at; i < n; i += step) tgt_count[i] = 0;
+    if (at == 0) *cursor = 0;
 }
 
 // plane widths (64-bit words) the selection kernels are compiled for (a lane keeps a whole code in registers: 4 x width
@@ -269,32 +301,33 @@ int build_width_at_least(int nw, int encoding) {
 }
 
 template <int ENC, int NW_T>
-static hipError_t launch_batch(const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
-                               hipStream_t stream) {
+static hipError_t launch_batch(const BuildParams& bp, hipStream_t stream) {
     hipLaunchKernelGGL((forward_select_kernel<ENC, NW_T>), dim3((unsigned)bp.bs), dim3(64), 0, stream, bp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const int64_t n_pairs = bp.bs * bp.R;
-    e = hipcub::DeviceRadixSort::SortKeys(temp, temp_bytes, bp.pairs, sorted, (int)n_pairs, 0, 64, stream);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((reverse_kernel<ENC, NW_T>), dim3((unsigned)n_pairs), dim3(64), 0, stream, bp, sorted, n_pairs);
+    const int64_t n_edges = bp.bs * bp.R;
+    const dim3 per_edge((unsigned)((n_edges + 255) / 256));
+    hipLaunchKernelGGL(reserve_segments_kernel, per_edge, dim3(256), 0, stream, bp, n_edges);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(scatter_sources_kernel, per_edge, dim3(256), 0, stream, bp, n_edges);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((reverse_kernel<ENC, NW_T>), dim3((unsigned)n_edges), dim3(64), 0, stream, bp);
     return hipGetLastError();
 }
 
-hipError_t launch_build_batch(int nw, int encoding, const BuildParams& bp, uint64_t* sorted, void* temp, size_t temp_bytes,
-                              hipStream_t stream) {
+hipError_t launch_build_batch(int nw, int encoding, const BuildParams& bp, hipStream_t stream) {
     if (encoding == ENC_SIGN1) {
-        if (nw == 2) return launch_batch<ENC_SIGN1, 2>(bp, sorted, temp, temp_bytes, stream);
-        if (nw == 12) return launch_batch<ENC_SIGN1, 12>(bp, sorted, temp, temp_bytes, stream);
+        if (nw == 2) return launch_batch<ENC_SIGN1, 2>(bp, stream);
+        if (nw == 12) return launch_batch<ENC_SIGN1, 12>(bp, stream);
         return hipErrorInvalidValue;
     }
     if (encoding == ENC_SQ2) {
-        if (nw == 2) return launch_batch<ENC_SQ2, 2>(bp, sorted, temp, temp_bytes, stream);
-        if (nw == 12) return launch_batch<ENC_SQ2, 12>(bp, sorted, temp, temp_bytes, stream);
+        if (nw == 2) return launch_batch<ENC_SQ2, 2>(bp, stream);
+        if (nw == 12) return launch_batch<ENC_SQ2, 12>(bp, stream);
         return hipErrorInvalidValue;
     }
     switch (nw) {
-#define QV_CASE(W) case W: return launch_batch<ENC_SM, W>(bp, sorted, temp, temp_bytes, stream);
+#define QV_CASE(W) case W: return launch_batch<ENC_SM, W>(bp, stream);
         QV_BUILD_SM_WIDTHS(QV_CASE)
 #undef QV_CASE
         default: return hipErrorInvalidValue;
@@ -320,8 +353,8 @@ static size_t padded_codes_bytes(int64_t n, int nw, int encoding) {
 
 size_t build_workspace_bytes(int64_t n, int nw, int encoding, int R, int L, int64_t max_batch) {
     const int64_t mb = build_max_batch(n, max_batch);
-    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 8) * 2 +
-           up256(build_sort_temp_bytes(mb * R)) + padded_codes_bytes(n, nw, encoding) + 256;
+    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 4) * 3 +
+           up256((size_t)n * 4) * 2 + 256 + padded_codes_bytes(n, nw, encoding) + 256;
 }
 
 hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
@@ -344,16 +377,17 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     uint32_t* cand_dist = reinterpret_cast<uint32_t*>(ws);  ws += up256((size_t)mb * L * 4);
     uint32_t* n_cand = reinterpret_cast<uint32_t*>(ws);     ws += up256((size_t)mb * 4);
     uint32_t* order = reinterpret_cast<uint32_t*>(ws);      ws += up256((size_t)mb * 4);
-    uint64_t* pairs = reinterpret_cast<uint64_t*>(ws);      ws += up256((size_t)mb * R * 8);
-    uint64_t* sorted = reinterpret_cast<uint64_t*>(ws);     ws += up256((size_t)mb * R * 8);
-    const size_t temp_bytes = build_sort_temp_bytes(mb * R);
-    void* temp = ws;
+    uint32_t* edge_target = reinterpret_cast<uint32_t*>(ws);  ws += up256((size_t)mb * R * 4);
+    uint32_t* edge_rank = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)mb * R * 4);
+    uint32_t* sources = reinterpret_cast<uint32_t*>(ws);      ws += up256((size_t)mb * R * 4);
+    uint32_t* tgt_count = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)n * 4);
+    uint32_t* tgt_start = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)n * 4);
+    uint32_t* cursor = reinterpret_cast<uint32_t*>(ws);
 
-    // every slot starts empty (a kernel, not a memset node: the whole call may be captured into a graph)
     {
         const int64_t words = n * (int64_t)R;
         const unsigned blocks = (unsigned)((words + 256 * 8 - 1) / (256 * 8) < 256 * 16 ? (words + 256 * 8 - 1) / (256 * 8) : 256 * 16);
-        hipLaunchKernelGGL(fill_empty_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, adj, words);
+        hipLaunchKernelGGL(fill_empty_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, adj, words, tgt_count, n, cursor);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -365,7 +399,9 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     plan_visited_table(sp, 4096, true, true);  // visited set as a cache: same lists, more queries per compute unit
     BuildParams bp{};
     bp.codes = codes; bp.adj = adj; bp.n = n; bp.R = R; bp.L = L; bp.alpha = alpha;
-    bp.cand_ids = cand_ids; bp.cand_dist = cand_dist; bp.n_cand = n_cand; bp.pairs = pairs;
+    bp.cand_ids = cand_ids; bp.cand_dist = cand_dist; bp.n_cand = n_cand;
+    bp.edge_target = edge_target; bp.edge_rank = edge_rank; bp.sources = sources; bp.tgt_count = tgt_count;
+    bp.tgt_start = tgt_start; bp.cursor = cursor;
     for (int64_t done = 0; done < n;) {
         int64_t bs = done / 50;
         if (bs < 1) bs = 1;
@@ -378,7 +414,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
         e = launch_beam_search(sp, 0, stream);
         if (e != hipSuccess) return e;
         bp.done = done; bp.bs = bs;
-        e = launch_build_batch(nw, encoding, bp, sorted, temp, temp_bytes, stream);
+        e = launch_build_batch(nw, encoding, bp, stream);
         if (e != hipSuccess) return e;
         done += bs;
     }

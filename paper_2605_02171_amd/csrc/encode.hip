@@ -331,29 +331,78 @@ __global__ void bq_distance_kernel(const uint64_t* __restrict__ a, const int64_t
     out[p] = c1 + c2 + 2u * c3;
 }
 
-// Measurement aid: every wave reads 64 rows of 2W words per round, rows named by ids[], with the access
-// pattern of the search kernel's code gather (4 lanes per row, 8-byte loads) and no arithmetic beyond an
-// XOR fold, so its rate is what the memory system gives to that pattern.
+// Measurement aid: every wave reads 64 rows of 2*NW words per round, rows named by ids[], with the access pattern
+// of the search kernel's code gather for that width -- G lanes per row, lane s of a group taking a contiguous
+// share of each plane in 16-byte loads when the shares are an even number of words (768-d: two lanes per row, three
+// 16-byte loads per plane and lane), words s, s+G, ... in 8-byte loads otherwise; as many of the G passes in flight
+// as the search kernel keeps -- and no arithmetic beyond an XOR fold, so its rate is what the memory system gives
+// to that pattern.  NW = 0: any width, 4 lanes per row, 8-byte loads.
+template <int NW, int G>
 __global__ __launch_bounds__(64) void gather_probe_kernel(const uint64_t* __restrict__ codes, int row_words,
                                                           const uint32_t* __restrict__ ids, int64_t n_ids,
                                                           uint64_t* __restrict__ sink) {
-    const int lane = threadIdx.x, sub = lane & 3, grp = lane >> 2;
+    const int lane = threadIdx.x;
     uint64_t acc = 0;
-    for (int64_t base = (int64_t)blockIdx.x * 64; base + 64 <= n_ids; base += (int64_t)gridDim.x * 64) {
-        const uint32_t mine = ids[base + lane];
-        for (int w0 = sub; w0 < row_words; w0 += 24) {
-            uint64_t t[4][6];  // up to 24 loads in flight per lane, as in the search kernel
+    if constexpr (NW > 0) {
+        constexpr int RPP = 64 / G, KW = (NW + G - 1) / G;
+        constexpr int BATCH = (2 * KW * G <= 48) ? G : (48 / (2 * KW) > 0 ? 48 / (2 * KW) : 1);
+        constexpr bool BLOCKED = BATCH == G && G <= 4 && NW % (2 * G) == 0;
+        const int sub = lane % G, grp = lane / G;
+        for (int64_t base = (int64_t)blockIdx.x * 64; base + 64 <= n_ids; base += (int64_t)gridDim.x * 64) {
+            const uint32_t mine = ids[base + lane];
+            for (int b0 = 0; b0 < G; b0 += BATCH) {
+                uint64_t pv[BATCH][KW], sv[BATCH][KW];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t row = (uint32_t)__shfl((int)mine, b * 16 + grp);
-                const uint64_t* p = codes + (int64_t)row * row_words;
+                for (int b = 0; b < BATCH; ++b) {
+                    if (b0 + b >= G) {   // wave-uniform: the last batch may be partial
 #pragma unroll
-                for (int u = 0; u < 6; ++u) t[b][u] = w0 + 4 * u < row_words ? p[w0 + 4 * u] : 0ull;
+                        for (int i = 0; i < KW; ++i) pv[b][i] = sv[b][i] = 0ull;
+                        continue;
+                    }
+                    const uint32_t r = (uint32_t)__shfl((int)mine, (b0 + b) * RPP + grp);
+                    const uint64_t* row = codes + (int64_t)r * (2 * NW);
+                    if constexpr (BLOCKED) {
+                        const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
+                        const uint4* m4 = reinterpret_cast<const uint4*>(row + NW + sub * KW);
+#pragma unroll
+                        for (int i = 0; i < KW / 2; ++i) {
+                            const uint4 a = r4[i], c = m4[i];
+                            pv[b][2 * i] = ((uint64_t)a.y << 32) | a.x; pv[b][2 * i + 1] = ((uint64_t)a.w << 32) | a.z;
+                            sv[b][2 * i] = ((uint64_t)c.y << 32) | c.x; sv[b][2 * i + 1] = ((uint64_t)c.w << 32) | c.z;
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < KW; ++i) {
+                            const int w = sub + i * G;
+                            pv[b][i] = w < NW ? row[w] : 0ull;
+                            sv[b][i] = w < NW ? row[NW + w] : 0ull;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < BATCH; ++b)
+#pragma unroll
+                    for (int i = 0; i < KW; ++i) acc ^= pv[b][i] ^ sv[b][i];
             }
+        }
+    } else {
+        const int sub = lane & 3, grp = lane >> 2;
+        for (int64_t base = (int64_t)blockIdx.x * 64; base + 64 <= n_ids; base += (int64_t)gridDim.x * 64) {
+            const uint32_t mine = ids[base + lane];
+            for (int w0 = sub; w0 < row_words; w0 += 24) {
+                uint64_t t[4][6];
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t row = (uint32_t)__shfl((int)mine, b * 16 + grp);
+                    const uint64_t* p = codes + (int64_t)row * row_words;
 #pragma unroll
-                for (int u = 0; u < 6; ++u) acc ^= t[b][u];
+                    for (int u = 0; u < 6; ++u) t[b][u] = w0 + 4 * u < row_words ? p[w0 + 4 * u] : 0ull;
+                }
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int u = 0; u < 6; ++u) acc ^= t[b][u];
+            }
         }
     }
     if (acc == 0x0123456789ABCDEFull) sink[0] = acc;  // keeps the loads alive
@@ -372,6 +421,34 @@ __global__ __launch_bounds__(256) void pad_codes_kernel(const uint64_t* __restri
     }
 }
 
+// Dense Sign-Magnitude rows (nw sign words, nw magnitude words) -> the two arrays of the split layout (kernels.h):
+// out1 rows of split_stride1(nw) words = sign plane, first split_k1(nw) magnitude words, zeros; out2 rows of the remaining
+// magnitude words.  One thread per input word.
+__global__ __launch_bounds__(256) void split_codes_kernel(const uint64_t* __restrict__ codes, int64_t n, int nw,
+                                                          uint64_t* __restrict__ out1, uint64_t* __restrict__ out2) {
+    const int s1 = split_stride1(nw), k1 = split_k1(nw), s2 = split_stride2(nw);
+    const int64_t total = n * s1 + n * s2;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        if (i < n * s1) {
+            const int64_t row = i / s1;
+            const int at = (int)(i - row * s1);
+            out1[i] = at < nw + k1 ? codes[row * 2 * nw + at] : 0ull;    // sign words and the first magnitude words are contiguous
+        } else {
+            const int64_t j = i - n * s1, row = j / s2;
+            const int at = (int)(j - row * s2);
+            out2[j] = codes[row * 2 * nw + nw + k1 + at];
+        }
+    }
+}
+
+hipError_t launch_split_codes(const uint64_t* codes, int64_t n, int nw, uint64_t* out1, uint64_t* out2, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    int64_t blocks = (n * 2 * nw + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(split_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, codes, n, nw, out1, out2);
+    return hipGetLastError();
+}
+
 hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int nw, int planes, int plane_words, int stride, uint64_t* out,
                             hipStream_t stream) {
     if (n == 0) return hipSuccess;
@@ -386,8 +463,15 @@ hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids
     if (n_ids < 64) return hipSuccess;
     int64_t blocks = n_ids / 64;
     if (blocks > 256 * 40) blocks = 256 * 40;
-    hipLaunchKernelGGL(gather_probe_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, codes, 2 * ((d + 63) / 64), ids,
-                       n_ids, sink);
+    const int nw = (d + 63) / 64;
+    const dim3 grid((unsigned)blocks), block(64);
+    switch (nw) {   // the widths of the workloads, with the lanes per row the search kernel picks for them
+#define QV_PROBE(W, G) case W: hipLaunchKernelGGL((gather_probe_kernel<W, G>), grid, block, 0, stream, codes, 2 * nw, ids, n_ids, sink); break;
+        QV_PROBE(2, 2) QV_PROBE(4, 2) QV_PROBE(6, 2) QV_PROBE(8, 2) QV_PROBE(12, 2) QV_PROBE(16, 4) QV_PROBE(24, 4)
+        QV_PROBE(32, 4) QV_PROBE(48, 16)
+#undef QV_PROBE
+        default: hipLaunchKernelGGL((gather_probe_kernel<0, 4>), grid, block, 0, stream, codes, 2 * nw, ids, n_ids, sink);
+    }
     return hipGetLastError();
 }
 
