@@ -202,7 +202,10 @@ int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uin
  *    kernels keep a whole code in registers; wider: QV_ERR_UNSUPPORTED).  The kernels are compiled for planes of
  *    2, 4, 6, 8, 12, 16 and 24 words; codes of another width are copied into the workspace with zero words
  *    appended to every plane (n more rows of the next compiled width), which changes no distance.
- *    workspace device, 256-byte aligned, >= qv_build_workspace_bytes(n, d, R, L, max_batch)
+ *    workspace device, 256-byte aligned, >= qv_build_workspace_bytes(n, d, R, L, max_batch) (8 bytes per node for grouping
+ *              a batch's new edges by target, plus the lists of the largest batch)
+ *    max_batch >= 1; the largest batch, min(max(1, n / 50), max_batch) nodes, times R must stay below 2^31
+ *    (QV_ERR_INVALID_ARG otherwise: lower max_batch).
  * All work is queued on `stream`; the call returns when everything is queued.
  */
 size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch);   /* 0: arguments out of range */
@@ -297,6 +300,33 @@ int qv_code_layout(int d, int encoding, int* plane_words, int* stride);
 int qv_pad_codes(const uint64_t* codes, int64_t n, int d, int encoding, int plane_words, int stride, uint64_t* out,
                  void* stream);
 int qv_index_set_code_layout(qv_index* index, int plane_words, int stride);
+
+/*
+ * Split layout of an index's codes (an option of this library; paper Sec. 3.1, Table 1 gives the bound it rests on,
+ * Sec. 4.2 "Cache friendliness" the cost it lowers: memory lines touched per hop).  A Sign-Magnitude distance is a
+ * sum over the dimensions whose signs differ of (1 + strong_q)(1 + strong_v) >= (1 + strong_q), so the sign plane of
+ * a node alone bounds its distance to the query from below.  A neighbour whose bound is not below the worst key of
+ * a full candidate list cannot enter it, whatever its magnitude bits are.  In the split layout the words of a row
+ * are stored in two arrays so that the bound costs as few 128-byte lines as possible:
+ *    array 1, rows of *words1 words (a multiple of 16 = 128 bytes): the sign plane, then as many of the first
+ *             magnitude words as fill the row's last line (768-d: 12 sign words + 4 magnitude words = one line);
+ *    array 2, rows of *words2 words: the remaining magnitude words (768-d: 8 words = 64 bytes).
+ * words1 + words2 = qv_code_words(d): same size as the dense rows.  The search kernel reads array 2 only for the
+ * neighbours that pass the bound, then completes the bound to the exact distance; lists, distances, expansion
+ * order and counters are bit for bit those of the dense layout (n_dist_evals counts a neighbour as evaluated
+ * whether or not its second part was read).
+ *   qv_split_layout           (host only) row lengths of the two arrays.  QV_ERR_UNSUPPORTED unless ceil(d/64) is 12, 16
+ *                             or 24 (768-d, 1024-d, 1536-d): shorter rows fit one line anyway (qv_code_layout), the
+ *                             kernel is not compiled for others.
+ *   qv_split_codes            dense rows (qv_encode's layout) -> the two arrays (device, caller's; out1 128-byte aligned,
+ *                             out2 16-byte aligned).  Asynchronous on `stream`.
+ *   qv_index_set_split_codes  gives an index its codes in this layout as well (both NULL: forget them).  Sign-Magnitude
+ *                             indexes only.  qv_search then gathers from these arrays with the kernel's own number of
+ *                             lanes per row; `codes` as given at load time is still read for the entry node.
+ */
+int qv_split_layout(int d, int* words1, int* words2);
+int qv_split_codes(const uint64_t* codes, int64_t n, int d, uint64_t* out1, uint64_t* out2, void* stream);
+int qv_index_set_split_codes(qv_index* index, const uint64_t* split1, const uint64_t* split2);
 
 const char* qv_strerror(int code);
 const char* qv_last_hip_error(void); /* text of the last failing HIP call in this thread, or "" */

@@ -97,6 +97,12 @@ _lib.qv_pad_codes.restype = ctypes.c_int
 _lib.qv_pad_codes.argtypes = [_P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _P, _P]
 _lib.qv_index_set_code_layout.restype = ctypes.c_int
 _lib.qv_index_set_code_layout.argtypes = [_P, ctypes.c_int, ctypes.c_int]
+_lib.qv_split_layout.restype = ctypes.c_int
+_lib.qv_split_layout.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+_lib.qv_split_codes.restype = ctypes.c_int
+_lib.qv_split_codes.argtypes = [_P, ctypes.c_int64, ctypes.c_int, _P, _P, _P]
+_lib.qv_index_set_split_codes.restype = ctypes.c_int
+_lib.qv_index_set_split_codes.argtypes = [_P, _P, _P]
 _lib.qv_search_workspace_bytes.restype = ctypes.c_size_t
 _lib.qv_search_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
 _lib.qv_search.restype = ctypes.c_int
@@ -196,6 +202,31 @@ def pad_codes(codes: torch.Tensor, d: int, layout: tuple[int, int] | None = None
     _check(_lib.qv_pad_codes(codes.data_ptr(), codes.shape[0], d, int(enc), pw, stride, out.data_ptr(), _stream()),
            "qv_pad_codes")
     return out
+
+
+def split_layout(d: int) -> tuple[int, int] | None:
+    """qv_split_layout: row lengths (64-bit words) of the two arrays of the split layout, or None where it does not apply."""
+    w1, w2 = ctypes.c_int(0), ctypes.c_int(0)
+    rc = _lib.qv_split_layout(int(d), ctypes.byref(w1), ctypes.byref(w2))
+    if rc == -9:
+        return None
+    _check(rc, "qv_split_layout")
+    return w1.value, w2.value
+
+
+def split_codes(codes: torch.Tensor, d: int) -> tuple[torch.Tensor, torch.Tensor]:
+    """qv_split_codes: dense Sign-Magnitude rows [n, cw] -> ([n, words1], [n, words2]) in the split layout."""
+    codes = _dev(codes, torch.int64, "codes")
+    if codes.dim() != 2 or codes.shape[1] != code_words(d):
+        raise ValueError("codes must be [n, code_words(d)]")
+    lay = split_layout(d)
+    if lay is None:
+        raise QuiverError(-9, "qv_split_layout")
+    n = codes.shape[0]
+    out1 = torch.empty((n, lay[0]), dtype=torch.int64, device=codes.device)
+    out2 = torch.empty((n, lay[1]), dtype=torch.int64, device=codes.device)
+    _check(_lib.qv_split_codes(codes.data_ptr(), n, int(d), out1.data_ptr(), out2.data_ptr(), _stream()), "qv_split_codes")
+    return out1, out2
 
 
 def bq_distance(codes_a: torch.Tensor, ia: torch.Tensor, codes_b: torch.Tensor, ib: torch.Tensor, d: int,
@@ -328,6 +359,19 @@ class Index:
             _check(_lib.qv_index_set_encoding(h, int(enc)), "qv_index_set_encoding")
         if layout is not None:
             _check(_lib.qv_index_set_code_layout(h, int(layout[0]), int(layout[1])), "qv_index_set_code_layout")
+
+    def set_split_codes(self, split: tuple[torch.Tensor, torch.Tensor] | None) -> None:
+        """qv_index_set_split_codes: the index's codes in the split layout as well (None: forget them)."""
+        if split is None:
+            _check(_lib.qv_index_set_split_codes(self._h, None, None), "qv_index_set_split_codes")
+            self._split = None
+            return
+        a, b = _dev(split[0], torch.int64, "split[0]"), _dev(split[1], torch.int64, "split[1]")
+        lay = split_layout(self.d)
+        if lay is None or a.shape != (self.n, lay[0]) or b.shape != (self.n, lay[1]):
+            raise ValueError("split arrays do not match the index")
+        _check(_lib.qv_index_set_split_codes(self._h, a.data_ptr(), b.data_ptr()), "qv_index_set_split_codes")
+        self._split = (a, b)
 
     def set_tuning(self, visited_slots: int = 0, lanes_per_row: int = 0, table_format: int = 0,
                    visited_mode: int = 0, rerank_mode: int = 0) -> None:

@@ -71,6 +71,8 @@ struct qv_index {
     int encoding;       // QV_ENC_*: what `codes` holds and what the queries are encoded to
     int code_plane_words;  // 64-bit words per bit-plane as stored in `codes`; 0: ceil(d / 64)
     int code_stride;    // 64-bit words between rows of `codes`; 0: dense
+    const uint64_t* split1;  // the codes again in the split layout (qv_index_set_split_codes), or null
+    const uint64_t* split2;
     qv_timer* timer;
 };
 
@@ -158,13 +160,20 @@ int qv_topk_overlap(const uint32_t* a, const uint32_t* b, int64_t nq, int K, uin
 static bool build_args_ok(int64_t n, int d, int R, int L) {
     return n >= 1 && n < 0xFFFFFFFFll && R >= 1 && R <= 64 && L >= 1 && L <= 192 && d >= 1 && d <= QV_MAX_DIM;
 }
+// one workgroup per selected edge of a batch: the largest batch, min(max(1, n / 50), max_batch) nodes, times R has to fit a grid
+static bool build_batch_ok(int64_t n, int R, int64_t max_batch) {
+    if (max_batch < 1) return false;
+    int64_t mb = n / 50 < 1 ? 1 : n / 50;
+    if (mb > max_batch) mb = max_batch;
+    return mb * R <= 0x7FFFFFFFll;
+}
 
 size_t qv_build_workspace_bytes(int64_t n, int d, int R, int L, int64_t max_batch) {
     return qv_build_workspace_bytes_enc(n, d, QV_ENC_SM, R, L, max_batch);
 }
 
 size_t qv_build_workspace_bytes_enc(int64_t n, int d, int encoding, int R, int L, int64_t max_batch) {
-    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !enc_ok(encoding)) return 0;
+    if (!build_args_ok(n, d, R, L) || !build_batch_ok(n, R, max_batch) || !enc_ok(encoding)) return 0;
     if (qv::build_width_at_least((d + 63) / 64, encoding) == 0) return 0;
     return qv::build_workspace_bytes(n, (d + 63) / 64, encoding, R, L, max_batch);
 }
@@ -177,7 +186,7 @@ int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double
 int qv_build_graph_enc(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
                        int64_t max_batch, uint32_t* adj, void* workspace, size_t workspace_bytes, void* stream) {
     if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
-    if (!build_args_ok(n, d, R, L) || max_batch < 1 || !(alpha >= 1.0) || (int64_t)entry >= n || !enc_ok(encoding))
+    if (!build_args_ok(n, d, R, L) || !build_batch_ok(n, R, max_batch) || !(alpha >= 1.0) || (int64_t)entry >= n || !enc_ok(encoding))
         return QV_ERR_INVALID_ARG;
     if (qv::build_width_at_least((d + 63) / 64, encoding) == 0) return QV_ERR_UNSUPPORTED;
     if (!codes || !adj) return QV_ERR_NULL;
@@ -197,7 +206,7 @@ int qv_index_load(qv_index** out, int64_t n, int d, int R, const uint32_t* adj, 
     qv_index* ix = new (std::nothrow) qv_index;
     if (!ix) return QV_ERR_NOMEM;
     ix->n = n; ix->d = d; ix->R = R; ix->adj = adj; ix->codes = codes; ix->vecs = vecs; ix->entry = entry;
-    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->rerank_mode = 0; ix->encoding = QV_ENC_SM; ix->code_plane_words = 0; ix->code_stride = 0; ix->timer = nullptr;
+    ix->visited_slots = 0; ix->lanes_per_row = 0; ix->table_format = 0; ix->visited_mode = 0; ix->rerank_mode = 0; ix->encoding = QV_ENC_SM; ix->code_plane_words = 0; ix->code_stride = 0; ix->split1 = ix->split2 = nullptr; ix->timer = nullptr;
     // where the cold data lives decides whether Stage 2 may run inside the search kernel (host memory: never)
     hipPointerAttribute_t attr;
     ix->vecs_on_device = true;
@@ -283,6 +292,41 @@ int qv_index_set_code_layout(qv_index* index, int plane_words, int stride) {
     if (!layout_ok(index->d, index->encoding, plane_words, stride)) return QV_ERR_INVALID_ARG;
     index->code_plane_words = plane_words;
     index->code_stride = stride;
+    return QV_OK;
+}
+
+int qv_split_layout(int d, int* words1, int* words2) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (!words1 || !words2) return QV_ERR_NULL;
+    const int nw = (d + 63) / 64;
+    if (qv::split_lanes_per_row(nw) == 0) return QV_ERR_UNSUPPORTED;
+    *words1 = qv::split_stride1(nw);
+    *words2 = qv::split_stride2(nw);
+    return QV_OK;
+}
+
+int qv_split_codes(const uint64_t* codes, int64_t n, int d, uint64_t* out1, uint64_t* out2, void* stream) {
+    if (d < 1 || d > QV_MAX_DIM) return QV_ERR_DIM;
+    if (n < 0) return QV_ERR_INVALID_ARG;
+    const int nw = (d + 63) / 64;
+    if (qv::split_lanes_per_row(nw) == 0) return QV_ERR_UNSUPPORTED;
+    if (n == 0) return QV_OK;
+    if (!codes || !out1 || !out2) return QV_ERR_NULL;
+    hipError_t e = qv::launch_split_codes(codes, n, nw, out1, out2, (hipStream_t)stream);
+    return e == hipSuccess ? QV_OK : hip_fail(e, "code split launch");
+}
+
+int qv_index_set_split_codes(qv_index* index, const uint64_t* split1, const uint64_t* split2) {
+    if (!index) return QV_ERR_NULL;
+    if (!split1 && !split2) {   // back to the rows given at load time
+        index->split1 = index->split2 = nullptr;
+        return QV_OK;
+    }
+    if (!split1 || !split2) return QV_ERR_NULL;
+    if (index->encoding != QV_ENC_SM || qv::split_lanes_per_row((index->d + 63) / 64) == 0) return QV_ERR_UNSUPPORTED;
+    if (((uintptr_t)split1 & 127u) || ((uintptr_t)split2 & 15u)) return QV_ERR_INVALID_ARG;
+    index->split1 = split1;
+    index->split2 = split2;
     return QV_OK;
 }
 
@@ -390,6 +434,9 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     qv::SearchParams sp;
     sp.adj = index->adj; sp.codes = index->codes; sp.qcodes = qcodes; sp.encoding = index->encoding;
     sp.row_stride = row_stride; sp.qstatus = qstatus;
+    // rows in the split layout are read by the search kernel only; they hold planes of ceil(d/64) words
+    const bool split = index->split1 && index->encoding == QV_ENC_SM && plane_words == nw;
+    sp.codes1 = split ? index->split1 : nullptr; sp.codes2 = split ? index->split2 : nullptr;
     sp.n = index->n; sp.nq = nq; sp.nw = plane_words; sp.R = index->R; sp.entry = index->entry; sp.ef = ef;
     // Visited set.  Default: a cache of 4096 slots (8 KB of 16-bit tags): with the list and the merge area a
     // query then needs about 10 KB of LDS, so 16 queries fit a compute unit and registers, not LDS, bound the

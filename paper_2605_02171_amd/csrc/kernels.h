@@ -14,9 +14,22 @@ constexpr uint32_t QV_STATUS_NONFINITE_BIT = 1u;
 constexpr uint32_t QV_STATUS_VISITED_FULL_BIT = 2u;
 constexpr uint32_t QV_STATUS_BAD_EDGE_BIT = 4u;
 
+// Split layout of Sign-Magnitude code rows longer than one 128-byte line (a rearrangement of the same words, same
+// total size).  First array: per row the whole sign plane, then the first split_k1(nw) magnitude words, which fill the
+// row up to a multiple of 128 bytes (split_stride1(nw) words).  Second array: the remaining magnitude words, dense.
+// The sign plane alone bounds a distance from below, so the search reads the second array only for neighbours that
+// the bound does not already keep out of the list.
+constexpr int split_stride1(int nw) { return (nw + 15) / 16 * 16; }
+constexpr int split_k1(int nw) { return split_stride1(nw) - nw < nw ? split_stride1(nw) - nw : nw; }
+constexpr int split_stride2(int nw) { return nw - split_k1(nw); }
+// widths the search kernel is compiled for in this layout, with the lanes per row it uses there (0: none)
+constexpr int split_lanes_per_row(int nw) { return nw == 12 ? 2 : ((nw == 16 || nw == 24) ? 4 : 0); }
+
 struct SearchParams {
     const uint32_t* adj;     // [n][R]
     const uint64_t* codes;   // [n] rows of code_row_words(nw, encoding) words, row_stride words apart
+    const uint64_t* codes1;  // split layout (see above), or null: [n][split_stride1(nw)] ...
+    const uint64_t* codes2;  // ... and [n][split_stride2(nw)]
     const uint64_t* qcodes;  // [nq][code_row_words(nw, encoding)]
     int encoding;            // ENC_*
     int row_stride;          // 64-bit words between the rows of `codes` (even, >= the row's words); qcodes are dense
@@ -73,6 +86,8 @@ hipError_t launch_pad_codes(const uint64_t* codes, int64_t n, int nw, int planes
                             hipStream_t stream);
 hipError_t launch_bq_distance(const uint64_t* a, const int64_t* ia, const uint64_t* b, const int64_t* ib,
                               int64_t npairs, int d, int encoding, uint32_t* out, hipStream_t stream);
+// dense Sign-Magnitude rows -> the two arrays of the split layout
+hipError_t launch_split_codes(const uint64_t* codes, int64_t n, int nw, uint64_t* out1, uint64_t* out2, hipStream_t stream);
 hipError_t launch_gather_probe(const uint64_t* codes, int d, const uint32_t* ids, int64_t n_ids, uint64_t* sink,
                                hipStream_t stream);
 int64_t bq_scan_chunk_rows(int64_t n);

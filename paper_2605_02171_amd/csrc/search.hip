@@ -512,7 +512,11 @@ __device__ __forceinline__ void rerank_own_list(const SearchParams& p, int64_t q
     }
 }
 
-template <int ENC, int NW_T, int G, int P, bool NARROW>
+// lanes `sub` of a group that ends up with the sum of pass b after the reduce-scatter below (and its inverse)
+template <int G>
+__device__ __forceinline__ constexpr int lane_of_pass(int b) { return G == 4 ? ((b >> 1) | ((b & 1) << 1)) : b; }
+
+template <int ENC, int NW_T, int G, int P, bool NARROW, bool SPLIT>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
     const int lane = threadIdx.x;
@@ -604,7 +608,102 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     auto process_list = [&](int m) {
         wave_sync();  // list[] written by other lanes
         uint64_t mine = KEY_NONE;
-        if constexpr (QUAD_REDUCE) {
+        if constexpr (SPLIT) {
+            // Two steps.  First the sign plane and the K1 magnitude words that share its lines: with the unknown
+            // magnitude words taken as zero, Table 1's sum is a lower bound of the distance (a differing sign then
+            // counts (1 + strong_q) instead of (1 + strong_q)(1 + strong_v)).  A neighbour whose bound is not below
+            // the list's worst key cannot enter the list whatever the rest of its code says, so the remaining
+            // magnitude words are read only for the others, and the bound is completed to the exact distance:
+            // per word the missing part is pc(X and s_v) + pc(X and s_v and s_q).
+            static_assert(QUAD_REDUCE && BLOCKED && ENC == ENC_SM, "split rows: two or four lanes per row, blocked words");
+            constexpr int K1 = split_k1(NW_T), S1 = split_stride1(NW_T), S2 = split_stride2(NW_T);
+            uint64_t worst = KEY_NONE;  // key of the last slot: KEY_NONE while the pool has room
+#pragma unroll
+            for (int r = 0; r < P; ++r)
+                if (r == ((ef - 1) >> 6)) worst = readlane64(pool.key[r], (ef - 1) & 63);
+            uint64_t xv[G][KW], sv[G][KW];
+#pragma unroll
+            for (int b = 0; b < G; ++b) {
+                if (b * RPP < m) {  // wave-uniform
+                    const int ri = min(b * RPP + grp, m - 1);
+                    const uint64_t* row = p.codes1 + (int64_t)list[ri] * S1;
+                    const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
+                    const uint4* m4 = reinterpret_cast<const uint4*>(row + NW_T + sub * KW);
+#pragma unroll
+                    for (int i = 0; i < KW / 2; ++i) {
+                        const uint4 a = r4[i];
+                        xv[b][2 * i] = ((uint64_t)a.y << 32) | a.x;
+                        xv[b][2 * i + 1] = ((uint64_t)a.w << 32) | a.z;
+                        uint4 c = make_uint4(0u, 0u, 0u, 0u);
+                        if (sub * KW + 2 * i < K1) c = m4[i];   // K1 is even: a pair of words is in one array or the other
+                        sv[b][2 * i] = ((uint64_t)c.y << 32) | c.x;
+                        sv[b][2 * i + 1] = ((uint64_t)c.w << 32) | c.z;
+                    }
+                }
+            }
+            uint32_t part[G];
+#pragma unroll
+            for (int b = 0; b < G; ++b) {
+                uint32_t c1 = 0, c2 = 0, c3 = 0;
+                if (b * RPP < m) {  // wave-uniform
+#pragma unroll
+                    for (int i = 0; i < KW; ++i) {
+                        sm_accumulate(xv[b][i], sv[b][i], qp[i], qs[i], c1, c2, c3);
+                        xv[b][i] ^= qp[i];   // the differing signs, kept for the second step
+                    }
+                }
+                part[b] = c1 + c2 + 2u * c3;
+            }
+            auto reduce_scatter = [&](const uint32_t* v, int& my_b) -> uint32_t {
+                if constexpr (G == 2) {
+                    const bool hi = sub & 1;
+                    my_b = hi ? 1 : 0;
+                    return (hi ? v[1] : v[0]) + quad_xor1(hi ? v[0] : v[1]);
+                } else {
+                    const bool o1 = sub & 1, o2 = sub & 2;
+                    const uint32_t k0 = (o1 ? v[2] : v[0]) + quad_xor1(o1 ? v[0] : v[2]);
+                    const uint32_t k1 = (o1 ? v[3] : v[1]) + quad_xor1(o1 ? v[1] : v[3]);
+                    my_b = (o1 ? 2 : 0) + (o2 ? 1 : 0);
+                    return (o2 ? k1 : k0) + quad_xor2(o2 ? k0 : k1);
+                }
+            };
+            int my_b;
+            uint32_t dist = reduce_scatter(part, my_b);
+            const int my_ri = my_b * RPP + grp;
+            const uint32_t my_id = my_ri < m ? list[my_ri] : 0u;
+            const uint64_t bound_key = ((uint64_t)dist << 33) | ((uint64_t)my_id << 1);
+            const uint64_t open = __ballot(my_ri < m && bound_key < worst);   // bit grp*G + lane_of_pass(b): row b*RPP + grp goes on
+            if (open) {
+                uint32_t rest[G];
+#pragma unroll
+                for (int b = 0; b < G; ++b) {
+                    rest[b] = 0;
+                    const bool go = (open >> (grp * G + lane_of_pass<G>(b))) & 1ull;
+                    if (__any(go)) {
+                        uint64_t s2[KW];
+                        const uint64_t* row = p.codes2 + (int64_t)list[min(b * RPP + grp, m - 1)] * S2;
+#pragma unroll
+                        for (int i = 0; i < KW / 2; ++i) {
+                            uint4 c = make_uint4(0u, 0u, 0u, 0u);
+                            const int w = sub * KW + 2 * i;
+                            if (go && w >= K1) c = *reinterpret_cast<const uint4*>(row + (w - K1));
+                            s2[2 * i] = ((uint64_t)c.y << 32) | c.x;
+                            s2[2 * i + 1] = ((uint64_t)c.w << 32) | c.z;
+                        }
+                        uint32_t e = 0;
+#pragma unroll
+                        for (int i = 0; i < KW; ++i) {
+                            const uint64_t t = xv[b][i] & s2[i];
+                            e += __popcll(t) + __popcll(t & qs[i]);
+                        }
+                        rest[b] = e;
+                    }
+                }
+                int same_b;
+                dist += reduce_scatter(rest, same_b);
+            }
+            if (my_ri < m) mine = ((uint64_t)dist << 33) | ((uint64_t)my_id << 1);
+        } else if constexpr (QUAD_REDUCE) {
             // pass b handles row b*RPP + grp; all loads first, then the arithmetic.  Lanes beyond the list load
             // the list's last row instead of being masked off (the line is in flight anyway, no branch, no
             // zero fill); what they compute is never used.
@@ -861,10 +960,10 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     }
 }
 
-template <int ENC, int NW_T, int G, int P, bool NARROW>
+template <int ENC, int NW_T, int G, int P, bool NARROW, bool SPLIT = false>
 static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
     size_t lds = beam_search_lds_bytes(p.nw, p.vis_slots, NARROW, p.ef);
-    auto kern = beam_search_kernel<ENC, NW_T, G, P, NARROW>;
+    auto kern = beam_search_kernel<ENC, NW_T, G, P, NARROW, SPLIT>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -876,6 +975,13 @@ static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
 
 template <int ENC, int NW_T, int G, int P>
 static hipError_t launch_n(const SearchParams& p, hipStream_t stream) {
+    if (p.codes1) {   // rows in the split layout: compiled for the Sign-Magnitude widths and lanes per row kernels.h names
+        if constexpr (ENC == ENC_SM && NW_T > 0 && split_lanes_per_row(NW_T) == G)
+            return p.vis_regions > 0 ? launch_one<ENC, NW_T, G, P, true, true>(p, stream)
+                                     : launch_one<ENC, NW_T, G, P, false, true>(p, stream);
+        else
+            return hipErrorInvalidValue;
+    }
     return p.vis_regions > 0 ? launch_one<ENC, NW_T, G, P, true>(p, stream) : launch_one<ENC, NW_T, G, P, false>(p, stream);
 }
 
@@ -1031,6 +1137,10 @@ hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStrea
     if (p.nq == 0) return hipSuccess;
     int g = lanes_per_row > 0 ? lanes_per_row : default_lanes_per_row(p.nw);
     if (g > 16) g = 16;
+    if (p.codes1) {
+        if (p.encoding != ENC_SM || split_lanes_per_row(p.nw) == 0) return hipErrorInvalidValue;
+        g = split_lanes_per_row(p.nw);
+    }
     if (p.encoding == ENC_SIGN1)
         return p.nw == 12 ? launch_beam_search_w<ENC_SIGN1, 12>(p, g, stream) : launch_beam_search_w<ENC_SIGN1, 0>(p, g, stream);
     if (p.encoding == ENC_SQ2)

@@ -562,3 +562,54 @@ def test_rerank_puts_non_finite_stored_vectors_last(qv):
             want_ids = np.stack([r[m] for r, m in zip(ref.ids, keep)])
             want_scores = np.stack([r[m] for r, m in zip(ref.scores, keep)])
             util.assert_topk_matches(ids[:, :n - 3], scores[:, :n - 3], want_ids, want_scores)
+
+
+@pytest.mark.parametrize("d,R,ef,k,n", [(768, 64, 64, 10, 20_000), (768, 64, 16, 10, 3_000), (768, 32, 200, 50, 20_000),
+                                        (1024, 64, 64, 10, 8_000), (1536, 48, 100, 10, 5_000), (768, 70, 1024, 100, 9_000),
+                                        (768, 64, 1, 1, 6_000)])
+def test_search_split_code_layout_is_bit_exact(qv, d, R, ef, k, n):
+    # the index's code rows in the split layout (sign plane first; the rest of the magnitude plane only for neighbours
+    # the sign-plane bound lets through): lists, distances, expansion order and counters as with dense rows
+    w = datagen.scaled("H2", n=n, nq=45, d=d)
+    x, q = datagen.make_base(w), datagen.make_queries(w)
+    rng = np.random.default_rng(d + ef)
+    x[n // 2: n // 2 + 30] = x[:30]               # repeated vectors: distance ties at the list's edge
+    adj = datagen.random_regular_graph(n, R, seed=d + R, fill=0.9) if R != 64 else graph.build_graph(x, 64, 64, 1.2)[0]
+    entry = 7
+    codes = oracle.encode(x, threads=8)
+    ref = oracle.search(q, adj, codes, x, entry, k, ef, visit_cap=1300, threads=8)
+    xd = torch.from_numpy(x).cuda()
+    gcodes = qv.encode(xd)
+    lay = qv.split_layout(d)
+    nw = (d + 63) // 64
+    assert lay is not None and sum(lay) == 2 * nw and lay[0] % 16 == 0
+    s1, s2 = qv.split_codes(gcodes, d)
+    # the two arrays hold the same words: sign plane, then magnitude words in order
+    h1, h2 = qv.to_numpy_u64(s1), qv.to_numpy_u64(s2)
+    k1 = lay[0] - nw
+    assert (h1[:, :nw] == codes[:, :nw]).all() and (h1[:, nw:] == codes[:, nw:nw + k1]).all()
+    assert (h2 == codes[:, nw + k1:]).all()
+    index = qv.Index(qv.from_numpy_u32(adj), gcodes, xd, entry)
+    index.set_split_codes((s1, s2))
+    qd = torch.from_numpy(q).cuda()
+    for visited_mode in (qv.VISITED_EXACT, qv.VISITED_CACHE):
+        for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED):
+            index.set_tuning(1024 if visited_mode == qv.VISITED_CACHE and ef <= 64 else 0, 0, 0, visited_mode, rerank_mode)
+            out = qv.search(index, qd, k, ef, trace=True, visit_cap=1300)
+            torch.cuda.synchronize()
+            _assert_search_equal(qv, ref, out, exact_counters=False)
+    index.set_split_codes(None)
+    index.set_tuning(0, 0, 0, qv.VISITED_EXACT)
+    out = qv.search(index, qd, k, ef, trace=True, visit_cap=1300)
+    torch.cuda.synchronize()
+    _assert_search_equal(qv, ref, out, exact_counters=False)
+
+
+def test_split_layout_applies_to_long_rows_only(qv):
+    for d in (64, 384, 512, 2048, 3072):
+        assert qv.split_layout(d) is None
+    assert qv.split_layout(768) == (16, 8) and qv.split_layout(1024) == (16, 16) and qv.split_layout(1536) == (32, 16)
+    codes = torch.zeros((10, 12), dtype=torch.int64, device="cuda")
+    with pytest.raises(qv.QuiverError) as e:
+        qv.split_codes(codes, 384)
+    assert e.value.code == -9
