@@ -49,6 +49,7 @@ extern "C" {
 #define QV_STATUS_VISITED_FULL 2u   /* search: the on-chip visited table filled up; results stay exact,     */
                                     /* n_dist_evals may count some nodes more than once                     */
 #define QV_STATUS_BAD_EDGE 4u       /* search: an adjacency entry >= n was skipped                          */
+#define QV_STATUS_TIMEOUT 8u        /* search: Stage 2 in other waves gave up waiting for the list (empty result) */
 
 /* Words (uint64) per code: 2 * ceil(d / 64); 0 if d is out of range.  Host only. */
 int qv_code_words(int d);
@@ -255,16 +256,24 @@ int qv_index_set_encoding(qv_index* index, int encoding);
  *                                      comes up again is evaluated again and dropped when it is merged
  *                    Either way status bit 2 of a query says that nodes may have been evaluated more than once.
  *    rerank_mode     where Stage 2 of Sec. 3.3 runs (same scores to the tolerance of the rerank, same order):
+ *                    QV_RERANK_SEPARATE  a kernel of its own after the search.
  *                    QV_RERANK_FUSED     inside the search kernel, by the wave that finished the query's Stage 1, so
  *                                        that its row reads fill the time other waves spend waiting for gathers.
- *                                        Only for ef <= 128 and vectors in device memory; elsewhere it is ignored.
- *                    QV_RERANK_SEPARATE  a kernel of its own after the search.
- *                    0: fused where it applies and a code row is at most 128 bytes long (d <= 512 for the 2-bit
- *                       codes), where it is the faster form; separate otherwise. */
+ *                    QV_RERANK_TAIL      inside the search kernel, by other waves: the launch holds one more workgroup
+ *                                        per query, which starts when the last searches are under way, waits for its
+ *                                        query's list if need be (the search it waits for is always running by then)
+ *                                        and scores it, so that Stage 2 fills the memory system the emptier end of
+ *                                        the batch leaves idle.  A wait that does not end within seconds (never seen)
+ *                                        is reported as status bit QV_STATUS_TIMEOUT with an empty result.
+ *                    The two in-kernel forms apply to ef <= 128 and vectors in device memory; elsewhere the stage runs
+ *                    as a kernel of its own.
+ *                    0: QV_RERANK_TAIL where a code row is at most 128 bytes long (d <= 512 for the 2-bit codes),
+ *                       QV_RERANK_SEPARATE otherwise. */
 #define QV_VISITED_EXACT 1
 #define QV_VISITED_CACHE 2
 #define QV_RERANK_SEPARATE 1
 #define QV_RERANK_FUSED 2
+#define QV_RERANK_TAIL 3
 int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, int table_format, int visited_mode,
                         int rerank_mode);
 /* 1 if a search with this beam width runs Stage 2 inside the search kernel as the index is set up now, else 0

@@ -25,6 +25,7 @@ VISITED_EXACT = 1
 VISITED_CACHE = 2
 RERANK_SEPARATE = 1
 RERANK_FUSED = 2
+RERANK_TAIL = 3
 ENC_SM, ENC_SIGN1, ENC_SQ2 = 0, 1, 2
 STATUS_NONFINITE = 1
 STATUS_VISITED_FULL = 2

@@ -13,6 +13,7 @@
 static_assert(QV_STATUS_NONFINITE == qv::QV_STATUS_NONFINITE_BIT, "status bits");
 static_assert(QV_STATUS_VISITED_FULL == qv::QV_STATUS_VISITED_FULL_BIT, "status bits");
 static_assert(QV_STATUS_BAD_EDGE == qv::QV_STATUS_BAD_EDGE_BIT, "status bits");
+static_assert(QV_STATUS_TIMEOUT == qv::QV_STATUS_TIMEOUT_BIT, "status bits");
 static_assert(QV_EMPTY == qv::EMPTY_ID, "empty id");
 
 namespace {
@@ -27,7 +28,7 @@ int hip_fail(hipError_t e, const char* where) {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WorkspaceLayout {
-    size_t qcodes, qcodes_wide, cand_ids, cand_dist, n_cand, order, qstatus, total;
+    size_t qcodes, qcodes_wide, cand_ids, cand_dist, n_cand, order, qstatus, rr_done, rr_ticket, total;
 };
 
 // widest plane (64-bit words) an index may store for vectors of nw words per plane: half as much again, plus two
@@ -43,6 +44,8 @@ WorkspaceLayout layout(int64_t nq, int d, int ef) {
     L.n_cand = off;    off = align_up(off + (size_t)nq * 4, 256);
     L.order = off;     off = align_up(off + (size_t)nq * 4, 256);
     L.qstatus = off;   off = align_up(off + (size_t)nq * 4, 256);
+    L.rr_done = off;   off = align_up(off + (size_t)nq * 4, 256);
+    L.rr_ticket = off; off += 256;
     L.total = off;
     return L;
 }
@@ -224,7 +227,7 @@ int qv_index_set_tuning(qv_index* index, int visited_slots, int lanes_per_row, i
     if (visited_slots != 0 && (visited_slots < 1024 || visited_slots > 28672)) return QV_ERR_INVALID_ARG;
     if (table_format != 0 && table_format != 32) return QV_ERR_INVALID_ARG;
     if (visited_mode != 0 && visited_mode != QV_VISITED_EXACT && visited_mode != QV_VISITED_CACHE) return QV_ERR_INVALID_ARG;
-    if (rerank_mode != 0 && rerank_mode != QV_RERANK_SEPARATE && rerank_mode != QV_RERANK_FUSED) return QV_ERR_INVALID_ARG;
+    if (rerank_mode != 0 && rerank_mode != QV_RERANK_SEPARATE && rerank_mode != QV_RERANK_FUSED && rerank_mode != QV_RERANK_TAIL) return QV_ERR_INVALID_ARG;
     if (lanes_per_row > 0 && (lanes_per_row > 16 || (lanes_per_row & (lanes_per_row - 1)))) return QV_ERR_INVALID_ARG;
     index->visited_slots = visited_slots;
     index->lanes_per_row = lanes_per_row;
@@ -330,16 +333,19 @@ int qv_index_set_split_codes(qv_index* index, const uint64_t* split1, const uint
     return QV_OK;
 }
 
-static bool rerank_is_fused(const qv_index* index, int ef, int row_words) {
-    const bool can_fuse = ef <= 128 && index->vecs_on_device;
-    return can_fuse && (index->rerank_mode == QV_RERANK_FUSED || (index->rerank_mode == 0 && row_words * 8 <= 128));
+// Where Stage 2 runs for this beam width: QV_RERANK_SEPARATE, QV_RERANK_FUSED or QV_RERANK_TAIL (see quiver.h).
+static int rerank_place(const qv_index* index, int ef, int row_words) {
+    const bool in_kernel_ok = ef <= 128 && index->vecs_on_device;
+    if (!in_kernel_ok || index->rerank_mode == QV_RERANK_SEPARATE) return QV_RERANK_SEPARATE;
+    if (index->rerank_mode != 0) return index->rerank_mode;
+    return row_words * 8 <= 128 ? QV_RERANK_TAIL : QV_RERANK_SEPARATE;
 }
 
 int qv_index_rerank_fused(const qv_index* index, int ef) {
     if (!index) return QV_ERR_NULL;
     const int planes = index->encoding == QV_ENC_SIGN1 ? 1 : 2;
     const int pw = index->code_stride > 0 ? index->code_plane_words : (index->d + 63) / 64;
-    return rerank_is_fused(index, ef, planes * pw) ? 1 : 0;
+    return rerank_place(index, ef, planes * pw) != QV_RERANK_SEPARATE ? 1 : 0;
 }
 
 size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef) {
@@ -456,19 +462,22 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     if (sp.vis_regions == 0 && sp.vis_slots > 8192) {  // 32-bit entries: keep the table within 32 KB of LDS
         qv::plan_visited_table(sp, 8192, false, cache);
     }
-    // Stage 2 inside the search kernel (beams of up to 128 entries over vectors in device memory): by default where a
-    // code row is at most one 128-byte line -- there the search waits on latency and the row reads of finished queries
-    // fill idle memory time (1M x 384: 1.21 -> 1.15 ms per 10,000 queries, 1M x 512: 1.27 -> 1.23) -- and not for wider
-    // rows, where the search already moves lines as fast as the memory system does and the two kernels stream better
-    // one after the other (1M x 768: 1.26 -> 1.32 ms, 1M x 3072: 4.66 -> 4.92).  When fused, the final lists leave the
-    // kernel only if the caller's trace asks for them.
-    const bool fused = rerank_is_fused(index, ef, planes * plane_words);
+    // Stage 2 inside the search launch (beams of up to 128 entries over vectors in device memory): by default where a
+    // code row is at most one 128-byte line, by other waves of the launch that start when the last searches are under
+    // way (QV_RERANK_TAIL).  Measured per 10,000 queries, ef = 64, kernel of its own / by the searching wave / by other
+    // waves: 1M x 384: 1.21 / 1.16 / 1.12 ms, 1M x 512: 1.27 / 1.22 / 1.19; with longer rows the search already moves
+    // lines as fast as the memory system does and nothing is gained (1M x 768: 1.26 / 1.33 / 1.25 ms), so there the
+    // stage stays a kernel of its own.  Inside the launch, the final lists leave it only if the caller's trace asks
+    // for them or other waves need them.
+    int place = rerank_place(index, ef, planes * plane_words);
+    if (place == QV_RERANK_TAIL && nq > (1ll << 30)) place = QV_RERANK_FUSED;   // two workgroups per query must fit a grid
+    const bool fused = place != QV_RERANK_SEPARATE, tail = place == QV_RERANK_TAIL;
     // the final lists go straight into the caller's trace buffers when there are any
     sp.cand_ids = trace && trace->cand_ids ? trace->cand_ids : reinterpret_cast<uint32_t*>(ws + L.cand_ids);
     sp.cand_dist = trace && trace->cand_dist ? trace->cand_dist : reinterpret_cast<uint32_t*>(ws + L.cand_dist);
     sp.n_cand = trace && trace->n_cand ? trace->n_cand : reinterpret_cast<uint32_t*>(ws + L.n_cand);
-    if (fused && !(trace && (trace->cand_ids || trace->cand_dist))) sp.cand_ids = sp.cand_dist = nullptr;
-    if (fused && !(trace && trace->n_cand)) sp.n_cand = nullptr;
+    if (fused && !tail && !(trace && (trace->cand_ids || trace->cand_dist))) sp.cand_ids = sp.cand_dist = nullptr;
+    if (fused && !tail && !(trace && trace->n_cand)) sp.n_cand = nullptr;
     sp.n_expanded = trace ? trace->n_expanded : nullptr;
     sp.n_evals = trace ? trace->n_dist_evals : nullptr;
     sp.status = trace ? trace->status : nullptr;
@@ -476,8 +485,11 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     sp.visit_cap = trace && trace->visit_order ? trace->visit_cap : 0;
     sp.rr_queries = fused ? queries : nullptr; sp.rr_vecs = fused ? index->vecs : nullptr;
     sp.rr_d = index->d; sp.rr_k = k; sp.rr_ids = ids; sp.rr_scores = scores;
+    sp.rr_ticket = tail ? reinterpret_cast<uint32_t*>(ws + L.rr_ticket) : nullptr;
+    sp.rr_done = tail ? reinterpret_cast<uint32_t*>(ws + L.rr_done) : nullptr;
+    sp.rr_spin_limit = 1u << 22;   // about seven seconds; a search takes milliseconds
     sp.order = nullptr;
-    if (qv::launch_query_order(sp, reinterpret_cast<uint32_t*>(ws + L.order), stream, &e))
+    if (qv::launch_query_order(sp, reinterpret_cast<uint32_t*>(ws + L.order), sp.rr_ticket, sp.rr_done, stream, &e))
         sp.order = reinterpret_cast<uint32_t*>(ws + L.order);
     if (e != hipSuccess) return hip_fail(e, "query order launch");
     if (ev && (e = hipEventRecord(ev[1], stream)) != hipSuccess) return hip_fail(e, "event record");

@@ -409,7 +409,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
         if (done + bs > n) bs = n - done;
         sp.qcodes = codes + done * (int64_t)code_row_words(nw, encoding);
         sp.nq = bs;
-        sp.order = launch_query_order(sp, order, stream, &e) ? order : nullptr;   // long searches first (large batches only)
+        sp.order = launch_query_order(sp, order, nullptr, nullptr, stream, &e) ? order : nullptr;   // long searches first (large batches only)
         if (e != hipSuccess) return e;
         e = launch_beam_search(sp, 0, stream);
         if (e != hipSuccess) return e;

@@ -13,6 +13,7 @@ __device__ inline int code_row_words_dev(int nw, int encoding) { return (encodin
 constexpr uint32_t QV_STATUS_NONFINITE_BIT = 1u;
 constexpr uint32_t QV_STATUS_VISITED_FULL_BIT = 2u;
 constexpr uint32_t QV_STATUS_BAD_EDGE_BIT = 4u;
+constexpr uint32_t QV_STATUS_TIMEOUT_BIT = 8u;
 
 // Split layout of Sign-Magnitude code rows longer than one 128-byte line (a rearrangement of the same words, same
 // total size).  First array: per row the whole sign plane, then the first split_k1(nw) magnitude words, which fill the
@@ -59,6 +60,17 @@ struct SearchParams {
     // Stage 2 inside the search kernel (rr_vecs != null; beams of up to 128 entries): the wave that finished a query
     // scores its final list at once, so that this streaming work fills the time in which other waves wait for their
     // gathers.  cand_ids / cand_dist / n_cand may then be null.
+    // Stage 2 by other waves of the same launch (rr_ticket != null, together with rr_vecs): the grid has 2 * nq
+    // workgroups; each takes a ticket from *rr_ticket when it starts.  Tickets below nq search query order[ticket];
+    // ticket nq + j scores the final list of query order[j] once rr_done says that it is in memory.  Whoever holds
+    // a scoring ticket started after every search ticket had been taken by a workgroup that is already running, so
+    // the wait always ends.  The scoring waves arrive when the last searches are under way and fill the memory system
+    // the emptier end of the batch leaves idle.  The list (cand_ids, n_cand: required) and the flag travel between
+    // the compute dies in device-coherent stores and loads; no cache is flushed or invalidated for them.
+    uint32_t* rr_ticket;      // [1], 0 before the launch
+    uint32_t* rr_done;        // [nq], 0 before the launch
+    uint32_t rr_spin_limit;   // polls (of about two microseconds) a scoring wave waits for its list before it gives up
+                              // and reports QV_STATUS_TIMEOUT_BIT with an empty result
     const float* rr_queries;  // [nq][rr_d]
     const float* rr_vecs;     // [n][rr_d]
     int rr_d, rr_k;
@@ -107,7 +119,9 @@ hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStrea
 // Fills order[nq] with a launch order of the queries: those whose code is farthest from the entry node's code
 // first (approximately).  Returns false (nothing launched) when the batch is too small or too large for it to
 // matter; then the caller passes no order.
-bool launch_query_order(const SearchParams& p, uint32_t* order, hipStream_t stream, hipError_t* err);
+// rr_ticket / rr_done (may be null): cleared by the same kernel for a launch with Stage 2 in other waves
+bool launch_query_order(const SearchParams& p, uint32_t* order, uint32_t* rr_ticket, uint32_t* rr_done, hipStream_t stream,
+                        hipError_t* err);
 // LDS bytes one query of the search kernel needs: visited table, two 64-entry lists, the merge scatter area
 // (64 keys per pool register of a lane, plus 64), the query code
 inline int beam_search_pool_registers(int ef) {

@@ -512,6 +512,52 @@ __device__ __forceinline__ void rerank_own_list(const SearchParams& p, int64_t q
     }
 }
 
+// Stage 2 by another wave of the same launch (SearchParams::rr_ticket).  The two waves may sit on different compute
+// dies, whose L2 caches do not see each other's ordinary stores until a kernel ends; flushing and invalidating those
+// caches per query (what a release / acquire fence at device scope does) costs more than the whole stage.  So what
+// has to travel -- the list's ids, its length, the flag -- is written and read with device-coherent accesses
+// (relaxed atomics at device scope: they go to the memory side of the L2s), ordered by waiting for the stores to
+// be acknowledged before the flag is written and for the flag to arrive before the list is read.
+__device__ __forceinline__ void coherent_store(uint32_t* at, uint32_t v) {
+    __hip_atomic_store(at, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t coherent_load(const uint32_t* at) {
+    return __hip_atomic_load(at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// the searching wave, after its coherent stores of the list: raise the query's flag
+__device__ __forceinline__ void publish_list(const SearchParams& p, int64_t q, int lane) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // every lane's stores of this wave are acknowledged
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) coherent_store(p.rr_done + q, 1u);
+}
+
+// The scoring wave: waits for the flag (the search it waits for is running, see SearchParams), reads the list from
+// memory into the register layout of a pool and scores it as rerank_own_list does.
+template <int NW_T, int P>
+__device__ __forceinline__ void score_finished_list(const SearchParams& p, int64_t q, int lane, uint64_t* lds) {
+    uint32_t ready = 0;
+    if (lane == 0) {
+        for (uint32_t polls = 0;; ++polls) {
+            ready = coherent_load(p.rr_done + q);
+            if (ready || polls >= p.rr_spin_limit) break;
+            __builtin_amdgcn_s_sleep(64);
+        }
+    }
+    ready = (uint32_t)__builtin_amdgcn_readfirstlane((int)ready);   // (waits for the flag's load)
+    asm volatile("" ::: "memory");
+    Pool<P> pool;
+    pool.size = ready ? (int)coherent_load(p.n_cand + q) : 0;
+#pragma unroll
+    for (int r = 0; r < P; ++r) {
+        const int e = r * 64 + lane;
+        pool.key[r] = e < pool.size ? (uint64_t)coherent_load(p.cand_ids + q * (int64_t)p.ef + e) << 1 : KEY_NONE;
+    }
+    // gave up (never seen in a working launch): an empty, flagged result
+    if (!ready && lane == 0 && p.status) p.status[q] = QV_STATUS_TIMEOUT_BIT;
+    rerank_own_list<NW_T, P>(p, q, pool, lane, lds);
+}
+
 // lanes `sub` of a group that ends up with the sum of pass b after the reduce-scatter below (and its inverse)
 template <int G>
 __device__ __forceinline__ constexpr int lane_of_pass(int b) { return G == 4 ? ((b >> 1) | ((b & 1) << 1)) : b; }
@@ -520,7 +566,20 @@ template <int ENC, int NW_T, int G, int P, bool NARROW, bool SPLIT>
 __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     extern __shared__ __align__(16) uint32_t smem[];
     const int lane = threadIdx.x;
-    const int64_t q = p.order ? (int64_t)p.order[blockIdx.x] : (int64_t)blockIdx.x;
+    int64_t slot = blockIdx.x;
+    if constexpr (P <= 2) {
+        if (p.rr_ticket) {   // roles by ticket, in the order in which workgroups start (see SearchParams)
+            uint32_t t = 0;
+            if (lane == 0) t = atomicAdd(p.rr_ticket, 1u);
+            slot = (int64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)t);
+            if (slot >= p.nq) {
+                score_finished_list<NW_T, P>(p, p.order ? (int64_t)p.order[slot - p.nq] : slot - p.nq, lane,
+                                             reinterpret_cast<uint64_t*>(smem));
+                return;
+            }
+        }
+    }
+    const int64_t q = p.order ? (int64_t)p.order[slot] : slot;
     const int NW = NW_T > 0 ? NW_T : p.nw;
     if (p.qstatus && (p.qstatus[q] & QV_STATUS_NONFINITE_BIT)) {   // wave-uniform
         // a query with Inf or NaN in it has no code to search with: empty list, no results, the flag in its status
@@ -530,17 +589,21 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
         }
         if (p.visit_order)
             for (int64_t i = lane; i < p.visit_cap; i += 64) p.visit_order[q * p.visit_cap + i] = EMPTY_ID;
-        if (p.rr_vecs)
+        if (p.rr_vecs && !p.rr_ticket)
             for (int r = lane; r < p.rr_k; r += 64) {
                 p.rr_ids[q * (int64_t)p.rr_k + r] = EMPTY_ID;
                 p.rr_scores[q * (int64_t)p.rr_k + r] = -__builtin_inff();
             }
         if (lane == 0) {
-            if (p.n_cand) p.n_cand[q] = 0;
+            if (p.n_cand) {
+                if (p.rr_ticket) coherent_store(p.n_cand + q, 0u);
+                else p.n_cand[q] = 0;
+            }
             if (p.n_expanded) p.n_expanded[q] = 0;
             if (p.n_evals) p.n_evals[q] = 0;
             if (p.status) p.status[q] = QV_STATUS_NONFINITE_BIT;
         }
+        if (p.rr_ticket) publish_list(p, q, lane);   // the scoring wave pads the result of an empty list
         return;
     }
     const uint32_t cap = p.vis_slots;   // slots (32-bit each, or 16-bit when NARROW)
@@ -940,7 +1003,9 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             int e = r * 64 + lane;
             if (e < ef) {
                 bool has = pool.key[r] != KEY_NONE;
-                cid[e] = has ? (uint32_t)(pool.key[r] >> 1) : EMPTY_ID;
+                const uint32_t id = has ? (uint32_t)(pool.key[r] >> 1) : EMPTY_ID;
+                if (P <= 2 && p.rr_ticket) coherent_store(cid + e, id);   // read by a wave that may sit on another die
+                else cid[e] = id;
                 cds[e] = has ? (uint32_t)(pool.key[r] >> 33) : EMPTY_ID;
             }
         }
@@ -948,15 +1013,21 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     status = (uint32_t)__builtin_amdgcn_readfirstlane((int)status) |
              (__any(status & QV_STATUS_BAD_EDGE_BIT) ? QV_STATUS_BAD_EDGE_BIT : 0u);
     if constexpr (P <= 2) {
-        if (p.rr_vecs) rerank_own_list<NW_T, P>(p, q, pool, lane, skeys);
+        if (p.rr_vecs && !p.rr_ticket) rerank_own_list<NW_T, P>(p, q, pool, lane, skeys);
     }
     if (lane == 0) {
-        if (p.n_cand) p.n_cand[q] = (uint32_t)pool.size;
+        if (p.n_cand) {
+            if (P <= 2 && p.rr_ticket) coherent_store(p.n_cand + q, (uint32_t)pool.size);
+            else p.n_cand[q] = (uint32_t)pool.size;
+        }
         if (p.n_expanded) p.n_expanded[q] = n_exp;
         if (p.n_evals) p.n_evals[q] = n_eval;
         if (p.status) p.status[q] = status;
         if (order)
             for (int64_t i = n_exp; i < p.visit_cap; ++i) order[i] = EMPTY_ID;
+    }
+    if constexpr (P <= 2) {
+        if (p.rr_ticket) publish_list(p, q, lane);
     }
 }
 
@@ -969,7 +1040,8 @@ static hipError_t launch_one(const SearchParams& p, hipStream_t stream) {
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)p.nq), dim3(64), lds, stream, p);
+    const bool two_roles = P <= 2 && p.rr_ticket != nullptr;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(two_roles ? 2 * p.nq : p.nq)), dim3(64), lds, stream, p);
     return hipGetLastError();
 }
 
@@ -1027,10 +1099,15 @@ constexpr int ORDER_BLOCK = 512;
 __global__ __launch_bounds__(ORDER_BLOCK) void query_order_kernel(const uint64_t* __restrict__ qcodes,
                                                                   const uint64_t* __restrict__ codes, int64_t nq, int nw,
                                                                   int encoding, uint32_t entry, int row_stride,
-                                                                  uint32_t* __restrict__ order) {
+                                                                  uint32_t* __restrict__ order,
+                                                                  uint32_t* __restrict__ rr_ticket,
+                                                                  uint32_t* __restrict__ rr_done) {
     __shared__ uint32_t keys[ORDER_BLOCK];
     const int tid = threadIdx.x;
     const int64_t q = (int64_t)blockIdx.x * ORDER_BLOCK + tid;
+    if (rr_done && q < nq) rr_done[q] = 0;       // state of a launch with Stage 2 in other waves: no list ready,
+    if (rr_ticket && q == 0) *rr_ticket = 0;     // no tickets taken
+    if (!order) return;                           // (uniform) a small batch: only that state is wanted
     uint32_t key = (uint32_t)(ORDER_BLOCK - 1 - tid);           // beyond the batch: below every real key
     if (q < nq) {
         const int rw = code_row_words_dev(nw, encoding);
@@ -1064,14 +1141,17 @@ __global__ __launch_bounds__(ORDER_BLOCK) void query_order_kernel(const uint64_t
     order[pos] = (uint32_t)q;
 }
 
-bool launch_query_order(const SearchParams& p, uint32_t* order, hipStream_t stream, hipError_t* err) {
+bool launch_query_order(const SearchParams& p, uint32_t* order, uint32_t* rr_ticket, uint32_t* rr_done, hipStream_t stream,
+                        hipError_t* err) {
     *err = hipSuccess;
     // fewer queries than resident waves all start at once; very large batches amortise their tail
-    if (p.nq < 4096 || p.nq > (1 << 20)) return false;
+    const bool ordered = p.nq >= 4096 && p.nq <= (1 << 20);
+    if (!ordered && !rr_ticket) return false;
     hipLaunchKernelGGL(query_order_kernel, dim3((unsigned)((p.nq + ORDER_BLOCK - 1) / ORDER_BLOCK)), dim3(ORDER_BLOCK), 0,
-                       stream, p.qcodes, p.codes, p.nq, p.nw, p.encoding, p.entry, p.row_stride, order);
+                       stream, p.qcodes, p.codes, p.nq, p.nw, p.encoding, p.entry, p.row_stride, ordered ? order : nullptr,
+                       rr_ticket, rr_done);
     *err = hipGetLastError();
-    return *err == hipSuccess;
+    return ordered && *err == hipSuccess;
 }
 
 // Picks the visited-table format for `slots` requested slots (rounded up to a multiple of 1024): 16-bit

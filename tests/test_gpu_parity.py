@@ -130,7 +130,7 @@ def _run_both(qv, x, q, adj, entry, k, ef, visit_cap=256, visited_slots=0, lanes
     torch.cuda.synchronize()
     assert torch.equal(plain.ids, cached.ids) and torch.equal(plain.scores, cached.scores)
     # Stage 2 as a kernel of its own and inside the search kernel (the default picks one of them by the row length)
-    for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED):
+    for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED, qv.RERANK_TAIL):
         index.set_tuning(0, lanes, table_format, 0, rerank_mode)
         other = qv.search(index, qd, k, ef, trace=True, visit_cap=visit_cap)
         torch.cuda.synchronize()
@@ -422,7 +422,8 @@ def test_search_with_cold_vectors_in_pinned_host_memory(qv):
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
-def test_search_replays_from_a_captured_graph(qv):
+@pytest.mark.parametrize("rerank_mode", [0, 3])
+def test_search_replays_from_a_captured_graph(qv, rerank_mode):
     # qv_search allocates nothing and records only kernels: with caller-owned workspace and outputs the whole call
     # can be captured once and replayed on new query contents; every replay must equal an eager call
     w = datagen.scaled("C3", n=20_000, nq=4500)          # above the launch-order threshold
@@ -430,6 +431,7 @@ def test_search_replays_from_a_captured_graph(qv):
     adj, entry = graph.build_graph(x, 32, 32, 1.2)
     xd = torch.from_numpy(x).cuda()
     index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, entry)
+    index.set_tuning(0, 0, 0, 0, rerank_mode)   # 3: Stage 2 by other waves of the search launch (tickets and flags in the workspace)
     k, ef = 10, 48
     rng = np.random.default_rng(5)
     static_q = torch.zeros((w.nq, w.d), dtype=torch.float32, device="cuda")
@@ -455,7 +457,8 @@ def test_search_replays_from_a_captured_graph(qv):
         assert torch.equal(out.n_expanded, eager.n_expanded), rep
 
 
-def test_searches_on_two_streams_at_once(qv):
+@pytest.mark.parametrize("rerank_mode", [0, 3])
+def test_searches_on_two_streams_at_once(qv, rerank_mode):
     # the index is read-only and all scratch lives in the caller's workspace: two searches with separate workspaces
     # may run on different streams at the same time (default stream priority); each must equal its own solo run
     w = datagen.scaled("C3", n=20_000, nq=4500)
@@ -463,6 +466,7 @@ def test_searches_on_two_streams_at_once(qv):
     adj, entry = graph.build_graph(x, 32, 32, 1.2)
     xd = torch.from_numpy(x).cuda()
     index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, entry)
+    index.set_tuning(0, 0, 0, 0, rerank_mode)
     rng = np.random.default_rng(11)
     qa = torch.from_numpy(rng.standard_normal((w.nq, w.d)).astype(np.float32)).cuda()
     qb = torch.from_numpy(rng.standard_normal((1500, w.d)).astype(np.float32)).cuda()
@@ -505,7 +509,7 @@ def test_search_reports_non_finite_queries_and_leaves_the_rest_exact(qv, d, ef):
     xd = torch.from_numpy(x).cuda()
     index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, 5)
     qd = torch.from_numpy(q).cuda()
-    for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED, 0):
+    for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED, qv.RERANK_TAIL, 0):
         for visited_mode in (qv.VISITED_EXACT, qv.VISITED_CACHE):
             index.set_tuning(0, 0, 0, visited_mode, rerank_mode)
             for trace in (True, False):
@@ -543,7 +547,7 @@ def test_rerank_puts_non_finite_stored_vectors_last(qv):
     xd = torch.from_numpy(dirty).cuda()
     index = qv.Index(qv.from_numpy_u32(adj), codes, xd, 0)
     ref = oracle.search(q, adj, oracle.encode(x), x, 0, n, ef)
-    for ef_run, mode in ((ef, qv.RERANK_SEPARATE), (128, qv.RERANK_FUSED), (128, qv.RERANK_SEPARATE)):
+    for ef_run, mode in ((ef, qv.RERANK_SEPARATE), (128, qv.RERANK_FUSED), (128, qv.RERANK_TAIL), (128, qv.RERANK_SEPARATE)):
         index.set_tuning(0, 0, 0, qv.VISITED_EXACT, mode)
         k = ef_run if ef_run < n else n
         out = qv.search(index, torch.from_numpy(q).cuda(), k, ef_run, trace=True)
@@ -593,7 +597,7 @@ def test_search_split_code_layout_is_bit_exact(qv, d, R, ef, k, n):
     index.set_split_codes((s1, s2))
     qd = torch.from_numpy(q).cuda()
     for visited_mode in (qv.VISITED_EXACT, qv.VISITED_CACHE):
-        for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED):
+        for rerank_mode in (qv.RERANK_SEPARATE, qv.RERANK_FUSED, qv.RERANK_TAIL):
             index.set_tuning(1024 if visited_mode == qv.VISITED_CACHE and ef <= 64 else 0, 0, 0, visited_mode, rerank_mode)
             out = qv.search(index, qd, k, ef, trace=True, visit_cap=1300)
             torch.cuda.synchronize()
