@@ -150,7 +150,8 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_index_set_tuning(h, 512, 0, 0, 0, 0) == -1 and lib.qv_index_set_tuning(h, 0, 3, 0, 0, 0) == -1
     assert lib.qv_index_set_tuning(h, 0, 0, 16, 0, 0) == -1 and lib.qv_index_set_tuning(h, 8192, 4, 32, 0, 0) == 0
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 3, 0) == -1 and lib.qv_index_set_tuning(h, 4096, 2, 0, 2, 0) == 0
-    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 3) == -1 and lib.qv_index_set_tuning(h, 0, 0, 0, 0, 1) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 4) == -1 and lib.qv_index_set_tuning(h, 0, 0, 0, 0, 3) == 0
+    assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 1) == 0
     assert lib.qv_index_set_tuning(h, 0, 0, 0, 0, 2) == 0
     # where Stage 2 runs: inside the search kernel for beams of up to 128 over short code rows (d = 8 here), unless told otherwise
     lib.qv_index_rerank_fused.argtypes = [P, ctypes.c_int]
