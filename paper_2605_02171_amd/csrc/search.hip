@@ -57,13 +57,21 @@ __device__ __forceinline__ uint32_t quad_xor2(uint32_t v) {
 // c1 += pc(X), c2 += pc(X and (s_v or s_q)), c3 += pc(X and s_v and s_q); distance = c1 + c2 + 2*c3.
 // The two masked terms are single three-input bit operations on gfx950 (truth tables 0xE0 = a&(b|c),
 // 0x80 = a&b&c with a = 0xF0, b = 0xCC, c = 0xAA).
+// popcount(x) + acc in one instruction (the bit-count instruction has an addend; written out because the compiler
+// otherwise counts into fresh registers and sums them with three-input adds, half as many instructions again)
+__device__ __forceinline__ uint32_t popc_add(uint32_t x, uint32_t acc) {
+    uint32_t r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(x), "v"(acc));
+    return r;
+}
+
 __device__ __forceinline__ void sm_accumulate(uint64_t pv, uint64_t sv, uint64_t pq, uint64_t sq, uint32_t& c1,
                                               uint32_t& c2, uint32_t& c3) {
     const uint32_t xl = (uint32_t)pv ^ (uint32_t)pq, xh = (uint32_t)(pv >> 32) ^ (uint32_t)(pq >> 32);
     const uint32_t svl = (uint32_t)sv, svh = (uint32_t)(sv >> 32), sql = (uint32_t)sq, sqh = (uint32_t)(sq >> 32);
-    c1 += __popc(xl) + __popc(xh);
-    c2 += __popc(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0xE0)) + __popc(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0xE0));
-    c3 += __popc(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0x80)) + __popc(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0x80));
+    c1 = popc_add(xh, popc_add(xl, c1));
+    c2 = popc_add(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0xE0), popc_add(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0xE0), c2));
+    c3 = popc_add(__builtin_amdgcn_bitop3_b32(xh, svh, sqh, 0x80), popc_add(__builtin_amdgcn_bitop3_b32(xl, svl, sql, 0x80), c3));
 }
 
 // The same step for any of the three encodings (ENC_SM: the method; ENC_SIGN1, ENC_SQ2: the two of the
@@ -198,7 +206,11 @@ __device__ __forceinline__ bool visited32_cache(uint32_t* tab, int bucket_bits, 
 }
 
 __device__ __forceinline__ bool visited16_cache(uint32_t* tab32, uint32_t regions, uint32_t B, uint32_t v, uint32_t clock,
-                                                bool& evicted) {
+                                                bool active, bool& evicted) {
+    // Straight-line body, repeated while any lane of the wave lost a compare-and-swap (two ids of one expansion
+    // that want the same slot: usual, since some sixty ids go into a few hundred buckets); lanes that are done,
+    // or were never `active`, are masked.  Ends: a failed compare-and-swap means another lane's succeeded, and a
+    // lane stops at its first success.
     const uint32_t r0 = v / 65535u;
     const uint32_t t0 = v - r0 * 65535u;
     uint32_t r = r0 + ((((t0 * 40503u) & 0xFFFFu) * regions) >> 16);
@@ -206,25 +218,30 @@ __device__ __forceinline__ bool visited16_cache(uint32_t* tab32, uint32_t region
     const uint32_t hb = (((v * 2654435761u) >> 16) * B) >> 16;
     const uint32_t pat = t0 * 0x00010001u;
     uint32_t* bp = tab32 + (r * B + hb) * 4;
-    for (;;) {  // ends for the same reason as above
-        const uint4 s = *reinterpret_cast<const uint4*>(bp);
-        if (any_zero_half(s.x ^ pat) | any_zero_half(s.y ^ pat) | any_zero_half(s.z ^ pat) | any_zero_half(s.w ^ pat))
-            return false;
-        int e = -1;
-        if (any_zero_half(~s.x)) e = 0;
-        else if (any_zero_half(~s.y)) e = 1;
-        else if (any_zero_half(~s.z)) e = 2;
-        else if (any_zero_half(~s.w)) e = 3;
-        const bool full = e < 0;
-        if (full) e = (int)((clock >> 1) & 3u);
+    const uint32_t victim = (clock >> 1) & 3u;
+    bool fresh = false, pending = active;
+    while (__any(pending)) {
+        uint4 s = make_uint4(0u, 0u, 0u, 0u);
+        if (pending) s = *reinterpret_cast<const uint4*>(bp);
+        const bool hit = (any_zero_half(s.x ^ pat) | any_zero_half(s.y ^ pat) | any_zero_half(s.z ^ pat) |
+                          any_zero_half(s.w ^ pat)) != 0u;
+        // first word with a free half, else the victim word
+        const uint32_t free_words = (any_zero_half(~s.x) ? 1u : 0u) | (any_zero_half(~s.y) ? 2u : 0u) |
+                                    (any_zero_half(~s.z) ? 4u : 0u) | (any_zero_half(~s.w) ? 8u : 0u);
+        const bool full = free_words == 0u;
+        const uint32_t e = full ? victim : (uint32_t)__builtin_ctz(free_words | 16u);
         const uint32_t word = e == 0 ? s.x : (e == 1 ? s.y : (e == 2 ? s.z : s.w));
         const bool low_half = full ? !(clock & 1u) : (word & 0xFFFFu) == 0xFFFFu;
         const uint32_t want = low_half ? ((word & 0xFFFF0000u) | t0) : ((word & 0xFFFFu) | (t0 << 16));
-        if (atomicCAS(bp + e, word, want) == word) {
-            evicted |= full;
-            return true;
-        }
+        const bool tries = pending && !hit;
+        uint32_t old = ~word;
+        if (tries) old = atomicCAS(bp + e, word, want);
+        const bool won = tries && old == word;
+        fresh |= won;
+        evicted |= won && full;
+        pending = tries && !won;
     }
+    return fresh;
 }
 
 template <int P>
@@ -775,7 +792,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             for (int b = 0; b < G; ++b) {
                 if (b * RPP < m) {  // wave-uniform
                     const int ri = min(b * RPP + grp, m - 1);
-                    const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
+                    const uint64_t* row = p.codes + (uint64_t)list[ri] * (uint32_t)p.row_stride;
                     if constexpr (BLOCKED) {
                         const uint4* r4 = reinterpret_cast<const uint4*>(row + sub * KW);
                         const uint4* m4 = reinterpret_cast<const uint4*>(row + NW_T + sub * KW);
@@ -841,7 +858,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     for (int b = 0; b < BATCH; ++b) {
                         int ri = base + b * RPP + grp;
                         if (ri < m) {
-                            const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
+                            const uint64_t* row = p.codes + (uint64_t)list[ri] * (uint32_t)p.row_stride;
 #pragma unroll
                             for (int i = 0; i < KW; ++i) {
                                 int w = sub + i * G;
@@ -874,7 +891,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
                     int ri = base + grp;
                     uint32_t c1 = 0, c2 = 0, c3 = 0;
                     if (ri < m) {
-                        const uint64_t* row = p.codes + (int64_t)list[ri] * p.row_stride;
+                        const uint64_t* row = p.codes + (uint64_t)list[ri] * (uint32_t)p.row_stride;
                         for (int w = sub; w < NW; w += G) {
                             code_accumulate<ENC>(row[w], PLANES == 2 ? row[NW + w] : 0ull, qlds[w], qlds[NW + w],
                                                  qlds[2 * NW + w], c1, c2, c3);
@@ -899,7 +916,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
         list[0] = p.entry;
         bool ignore = false;
         if (cache_mode) {
-            if constexpr (NARROW) visited16_cache(tab, vis_regions, vis_B, p.entry, 0u, ignore);
+            if constexpr (NARROW) visited16_cache(tab, vis_regions, vis_B, p.entry, 0u, true, ignore);
             else visited32_cache(tab, bucket_bits, p.entry, 0u, ignore);
         } else {
             if constexpr (NARROW) visited16_test_and_set(tab, vis_regions, vis_B, p.entry, true, ignore);
@@ -956,9 +973,10 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             bool fresh = false;
             if (cache_mode) {
                 bool evicted = false;
-                if (valid) {
-                    if constexpr (NARROW) fresh = visited16_cache(tab, vis_regions, vis_B, v, n_exp + (uint32_t)lane, evicted);
-                    else fresh = visited32_cache(tab, bucket_bits, v, n_exp + (uint32_t)lane, evicted);
+                if constexpr (NARROW) {
+                    fresh = visited16_cache(tab, vis_regions, vis_B, valid ? v : 0u, n_exp + (uint32_t)lane, valid, evicted);
+                } else {
+                    if (valid) fresh = visited32_cache(tab, bucket_bits, v, n_exp + (uint32_t)lane, evicted);
                 }
                 if (!vis_full && __any(evicted)) {  // from now on a node may come back: merges check for duplicates
                     vis_full = true;
