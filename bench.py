@@ -87,10 +87,10 @@ def main() -> int:
     ap.add_argument("--encoding", choices=("sm", "sign1", "sq2"), default="sm",
                     help="sm: the method; sign1 / sq2: the paper's ablation encodings (graph built on the GPU in that "
                          "encoding's own distance, so --graph gpu is implied and there is no CPU leg)")
-    ap.add_argument("--index-layout", choices=("dense", "recommended", "split"), default="dense",
-                    help="recommended: the index's code rows in the layout qv_code_layout names (planes padded to a "
-                         "compiled kernel width, rows aligned to 128-byte lines); differs from dense rows only at "
-                         "some widths, e.g. 384-d and 960-d.  split: sign plane first, the rest of the magnitude "
+    ap.add_argument("--index-layout", choices=("dense", "recommended", "split"), default="recommended",
+                    help="recommended (default): the index's code rows in the layout qv_code_layout names (planes padded "
+                         "to a compiled kernel width, rows aligned to 128-byte lines); differs from dense rows only at "
+                         "some widths, e.g. 384-d and 960-d, not at 768-d.  split: sign plane first, the rest of the magnitude "
                          "plane in a second array that is read only for neighbours the sign-plane bound lets through "
                          "(768-d, 1024-d, 1536-d)")
     ap.add_argument("--cold-host", action="store_true",
@@ -397,7 +397,7 @@ def main() -> int:
                        args.visited_mode or args.rerank_mode or args.cold_host) and args.graph == "host" and enc == qv.ENC_SM
     if split is not None:
         tpath = tpath.replace(".json", "_split.json")
-    if os.path.exists(tpath) and default_run and index_codes is codes:
+    if os.path.exists(tpath) and default_run and args.index_layout != "dense":
         with open(tpath) as f:
             tj = json.load(f)
         if tj.get("kernel_source_sha256") == kernel_source_digest():

@@ -224,10 +224,10 @@ int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double
  *                  this form (a constant vector has level 3 everywhere).  Two bit-planes, low bit of the level
  *                  first, packed like the Sign-Magnitude planes.
  * qv_index_set_encoding tells an index which encoding its `codes` are in (queries are then encoded the same way).
- * Widths: encode, distance, scan and search take any d; qv_build_graph_enc takes d <= 768 for the two ablation
- * encodings (compiled for planes of 2 and 12 words, other widths zero-padded in the workspace; wider:
- * QV_ERR_UNSUPPORTED); its workspace is qv_build_workspace_bytes_enc.  An unknown encoding is QV_ERR_INVALID_ARG (0 words from
- * qv_code_words_enc).
+ * Widths: encode, distance, scan and search take any d (the search kernel is compiled for the same plane widths in all
+ * three encodings; at widths other than 768-d the ablation encodings use the default number of lanes per row whatever
+ * qv_index_set_tuning says); qv_build_graph_enc takes d <= 1536 like qv_build_graph; its workspace is
+ * qv_build_workspace_bytes_enc.  An unknown encoding is QV_ERR_INVALID_ARG (0 words from qv_code_words_enc).
  */
 #define QV_ENC_SM 0
 #define QV_ENC_SIGN1 1

@@ -11,8 +11,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libquiver_hip.so")
 SOURCES = ["api.hip", "encode.hip", "rerank.hip", "scan.hip", "build.hip"]
 # the search kernel is compiled once per (encoding, code width) pair (64-bit words per bit-plane; 0 = any width
-# at run time); the ablation encodings 1 and 2 exist for 768-d and for the run-time width only
-SEARCH_VARIANTS = [(0, 12), (0, 16), (0, 24), (0, 48), (0, 32), (0, 8), (0, 6), (0, 4), (0, 2), (0, 0), (1, 12), (2, 12), (1, 0), (2, 0)]
+# at run time), for each of the three encodings
+SM_WIDTHS = [12, 16, 24, 48, 32, 8, 6, 4, 2, 0]
+SEARCH_VARIANTS = [(0, w) for w in SM_WIDTHS] + [(e, w) for e in (1, 2) for w in SM_WIDTHS]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-parameter",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

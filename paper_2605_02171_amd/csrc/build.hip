@@ -138,6 +138,8 @@ struct BuildParams {
     uint32_t* edge_rank;        // [bs*R] how many edges had counted themselves in at the same target before e
     uint32_t* tgt_count;        // [n]    edges of this batch per target; 0 outside the reverse step
     uint32_t* tgt_start;        // [n]    where the target's sources start in `sources`
+    uint32_t* edge_start;       // [bs*R] for the edge of rank 0 at a target: tgt_start and ...
+    uint32_t* edge_count;       // [bs*R] ... tgt_count of that target (what the reverse step needs, next to the edge)
     uint32_t* sources;          // [bs*R] sources, one segment per target
     uint32_t* cursor;           // [1]    words of `sources` reserved so far; 0 between batches
 };
@@ -193,7 +195,10 @@ __global__ __launch_bounds__(256) void reserve_segments_kernel(BuildParams p, in
     if (e >= n_edges) return;
     const uint32_t b = p.edge_target[e];
     if (b == EMPTY_ID || p.edge_rank[e] != 0) return;
-    p.tgt_start[b] = atomicAdd(p.cursor, p.tgt_count[b]);
+    const uint32_t count = p.tgt_count[b], start = atomicAdd(p.cursor, count);
+    p.tgt_start[b] = start;
+    p.edge_start[e] = start;
+    p.edge_count[e] = count;
 }
 
 // one thread per edge: the source (batch node e / R) goes to its place in the target's segment
@@ -215,8 +220,8 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p) {
     const int64_t e0 = blockIdx.x;
     const uint32_t b = p.edge_target[e0];
     if (b == EMPTY_ID || p.edge_rank[e0] != 0) return;   // only the edge of rank 0 works on its target
-    const int64_t n_src = p.tgt_count[b];
-    const uint32_t* src = p.sources + p.tgt_start[b];
+    const int64_t n_src = p.edge_count[e0];
+    const uint32_t* src = p.sources + p.edge_start[e0];
     if (lane == 0) p.tgt_count[b] = 0;                   // left as the next batch expects it
 
     const uint32_t v = lane < p.R ? p.adj[(int64_t)b * p.R + lane] : EMPTY_ID;
@@ -292,7 +297,7 @@ __global__ void fill_empty_kernel(uint32_t* __restrict__ adj, int64_t words, uin
 #define QV_BUILD_SM_WIDTHS(X) X(2) X(4) X(6) X(8) X(12) X(16) X(24)
 
 int build_width_at_least(int nw, int encoding) {
-    if (encoding != ENC_SM) return nw <= 2 ? 2 : (nw <= 12 ? 12 : 0);
+    (void)encoding;   // every encoding is compiled for the same widths
     int best = 0;
 #define QV_PICK(W) if (best == 0 && W >= nw) best = W;
     QV_BUILD_SM_WIDTHS(QV_PICK)
@@ -316,22 +321,21 @@ static hipError_t launch_batch(const BuildParams& bp, hipStream_t stream) {
 }
 
 hipError_t launch_build_batch(int nw, int encoding, const BuildParams& bp, hipStream_t stream) {
+#define QV_CASE_E(E, W) case W: return launch_batch<E, W>(bp, stream);
+#define QV_CASE_S1(W) QV_CASE_E(ENC_SIGN1, W)
+#define QV_CASE_SQ(W) QV_CASE_E(ENC_SQ2, W)
+#define QV_CASE_SM(W) QV_CASE_E(ENC_SM, W)
     if (encoding == ENC_SIGN1) {
-        if (nw == 2) return launch_batch<ENC_SIGN1, 2>(bp, stream);
-        if (nw == 12) return launch_batch<ENC_SIGN1, 12>(bp, stream);
-        return hipErrorInvalidValue;
+        switch (nw) { QV_BUILD_SM_WIDTHS(QV_CASE_S1) default: return hipErrorInvalidValue; }
     }
     if (encoding == ENC_SQ2) {
-        if (nw == 2) return launch_batch<ENC_SQ2, 2>(bp, stream);
-        if (nw == 12) return launch_batch<ENC_SQ2, 12>(bp, stream);
-        return hipErrorInvalidValue;
+        switch (nw) { QV_BUILD_SM_WIDTHS(QV_CASE_SQ) default: return hipErrorInvalidValue; }
     }
-    switch (nw) {
-#define QV_CASE(W) case W: return launch_batch<ENC_SM, W>(bp, stream);
-        QV_BUILD_SM_WIDTHS(QV_CASE)
-#undef QV_CASE
-        default: return hipErrorInvalidValue;
-    }
+    switch (nw) { QV_BUILD_SM_WIDTHS(QV_CASE_SM) default: return hipErrorInvalidValue; }
+#undef QV_CASE_S1
+#undef QV_CASE_SQ
+#undef QV_CASE_SM
+#undef QV_CASE_E
 }
 
 // ---- host loop -------------------------------------------------------------------------------
@@ -353,7 +357,7 @@ static size_t padded_codes_bytes(int64_t n, int nw, int encoding) {
 
 size_t build_workspace_bytes(int64_t n, int nw, int encoding, int R, int L, int64_t max_batch) {
     const int64_t mb = build_max_batch(n, max_batch);
-    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 4) * 3 +
+    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 4) * 5 +
            up256((size_t)n * 4) * 2 + 256 + padded_codes_bytes(n, nw, encoding) + 256;
 }
 
@@ -380,6 +384,8 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     uint32_t* edge_target = reinterpret_cast<uint32_t*>(ws);  ws += up256((size_t)mb * R * 4);
     uint32_t* edge_rank = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)mb * R * 4);
     uint32_t* sources = reinterpret_cast<uint32_t*>(ws);      ws += up256((size_t)mb * R * 4);
+    uint32_t* edge_start = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * R * 4);
+    uint32_t* edge_count = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * R * 4);
     uint32_t* tgt_count = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)n * 4);
     uint32_t* tgt_start = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)n * 4);
     uint32_t* cursor = reinterpret_cast<uint32_t*>(ws);
@@ -401,7 +407,7 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     bp.codes = codes; bp.adj = adj; bp.n = n; bp.R = R; bp.L = L; bp.alpha = alpha;
     bp.cand_ids = cand_ids; bp.cand_dist = cand_dist; bp.n_cand = n_cand;
     bp.edge_target = edge_target; bp.edge_rank = edge_rank; bp.sources = sources; bp.tgt_count = tgt_count;
-    bp.tgt_start = tgt_start; bp.cursor = cursor;
+    bp.tgt_start = tgt_start; bp.cursor = cursor; bp.edge_start = edge_start; bp.edge_count = edge_count;
     for (int64_t done = 0; done < n;) {
         int64_t bs = done / 50;
         if (bs < 1) bs = 1;

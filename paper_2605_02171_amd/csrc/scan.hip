@@ -204,23 +204,20 @@ hipError_t launch_bq_scan(const uint64_t* codes, int64_t n, int d, int encoding,
     const int64_t chunk = bq_scan_chunk_rows(n);
     const int nchunks = n > 0 ? (int)((n + chunk - 1) / chunk) : 0;
     hipError_t e = hipSuccess;
-    if (n > 0 && encoding == ENC_SIGN1) {
-        e = nw == 12 ? launch_scan_k<ENC_SIGN1, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream)
-                     : launch_scan_k<ENC_SIGN1, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream);
-        if (e != hipSuccess) return e;
-    } else if (n > 0 && encoding == ENC_SQ2) {
-        e = nw == 12 ? launch_scan_k<ENC_SQ2, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream)
-                     : launch_scan_k<ENC_SQ2, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream);
-        if (e != hipSuccess) return e;
-    } else if (n > 0) {
-        switch (nw) {
-            case 2: e = launch_scan_k<ENC_SM, 2>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 6: e = launch_scan_k<ENC_SM, 6>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 8: e = launch_scan_k<ENC_SM, 8>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 12: e = launch_scan_k<ENC_SM, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            case 16: e = launch_scan_k<ENC_SM, 16>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
-            default: e = launch_scan_k<ENC_SM, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break;
+    if (n > 0) {
+#define QV_SCAN_WIDTHS(E) \
+        switch (nw) { \
+            case 2: e = launch_scan_k<E, 2>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break; \
+            case 6: e = launch_scan_k<E, 6>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break; \
+            case 8: e = launch_scan_k<E, 8>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break; \
+            case 12: e = launch_scan_k<E, 12>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break; \
+            case 16: e = launch_scan_k<E, 16>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break; \
+            default: e = launch_scan_k<E, 0>(codes, n, nw, qcodes, nq, K, chunk, partial, stream); break; \
         }
+        if (encoding == ENC_SIGN1) { QV_SCAN_WIDTHS(ENC_SIGN1) }
+        else if (encoding == ENC_SQ2) { QV_SCAN_WIDTHS(ENC_SQ2) }
+        else { QV_SCAN_WIDTHS(ENC_SM) }
+#undef QV_SCAN_WIDTHS
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(bq_scan_merge_kernel, dim3((unsigned)nq), dim3(64), 0, stream, partial, nq, K, nchunks, ids, dist);

@@ -1087,6 +1087,11 @@ static hipError_t launch_p(const SearchParams& p, hipStream_t stream) {
 
 template <int ENC, int NW_T>
 static hipError_t launch_g(const SearchParams& p, int g, hipStream_t stream) {
+    // the ablation encodings at widths other than 768-d are compiled for one gather width only, the one picked by default
+    if constexpr (ENC != ENC_SM && NW_T != 0 && NW_T != 12) {
+        constexpr int GD = NW_T <= 12 ? 2 : (NW_T <= 32 ? 4 : 16);
+        return launch_p<ENC, NW_T, GD>(p, stream);
+    }
     switch (g) {
         case 1: return launch_p<ENC, NW_T, 1>(p, stream);
         case 2: return launch_p<ENC, NW_T, 2>(p, stream);
@@ -1201,7 +1206,8 @@ void plan_visited_table(SearchParams& p, uint32_t slots, bool allow_narrow, bool
 // This file is compiled once per (encoding, code width) pair (-DQV_SEARCH_ENC=e -DQV_SEARCH_WIDTH=w, w = 64-bit
 // words per bit-plane, 0 = any width at run time), so that the instantiations build in parallel; each
 // object exports launch_beam_search_w<e, w>, and the object for (ENC_SM, 0) also holds the dispatcher and the
-// table planner.  The ablation encodings exist for the widths 12 (768-d, the paper's ablation) and 0.
+// table planner.  The ablation encodings exist for the same widths (every gather width at 12 words = 768-d, the
+// paper's ablation, and at 0; the default gather width elsewhere).
 #if !defined(QV_SEARCH_WIDTH) || !defined(QV_SEARCH_ENC)
 #error "compile with -DQV_SEARCH_ENC=<encoding> -DQV_SEARCH_WIDTH=<words per plane> (see build.py)"
 #endif
@@ -1219,11 +1225,16 @@ template hipError_t launch_beam_search_w<QV_SEARCH_ENC, QV_SEARCH_WIDTH>(const S
 QV_SM_WIDTHS(QV_EXT_SM)
 #undef QV_EXT_SM
 #define QV_EXT(E, W) extern template hipError_t launch_beam_search_w<E, W>(const SearchParams&, int, hipStream_t);
-QV_EXT(ENC_SIGN1, 0) QV_EXT(ENC_SIGN1, 12) QV_EXT(ENC_SQ2, 0) QV_EXT(ENC_SQ2, 12)
+QV_EXT(ENC_SIGN1, 0) QV_EXT(ENC_SQ2, 0)
+#define QV_EXT_S1(W) QV_EXT(ENC_SIGN1, W)
+#define QV_EXT_SQ(W) QV_EXT(ENC_SQ2, W)
+QV_SM_WIDTHS(QV_EXT_S1) QV_SM_WIDTHS(QV_EXT_SQ)
+#undef QV_EXT_S1
+#undef QV_EXT_SQ
 #undef QV_EXT
 
 int search_compiled_width_at_least(int nw, int encoding) {
-    if (encoding != ENC_SM) return nw <= 12 ? 12 : 0;
+    (void)encoding;   // every encoding is compiled for the same widths
     int best = 0;
 #define QV_PICK(W) if (best == 0 && W >= nw) best = W;
     QV_SM_WIDTHS(QV_PICK)
@@ -1239,10 +1250,22 @@ hipError_t launch_beam_search(const SearchParams& p, int lanes_per_row, hipStrea
         if (p.encoding != ENC_SM || split_lanes_per_row(p.nw) == 0) return hipErrorInvalidValue;
         g = split_lanes_per_row(p.nw);
     }
-    if (p.encoding == ENC_SIGN1)
-        return p.nw == 12 ? launch_beam_search_w<ENC_SIGN1, 12>(p, g, stream) : launch_beam_search_w<ENC_SIGN1, 0>(p, g, stream);
-    if (p.encoding == ENC_SQ2)
-        return p.nw == 12 ? launch_beam_search_w<ENC_SQ2, 12>(p, g, stream) : launch_beam_search_w<ENC_SQ2, 0>(p, g, stream);
+    if (p.encoding == ENC_SIGN1) {
+        switch (p.nw) {
+#define QV_CASE(W) case W: return launch_beam_search_w<ENC_SIGN1, W>(p, g, stream);
+            QV_SM_WIDTHS(QV_CASE)
+#undef QV_CASE
+            default: return launch_beam_search_w<ENC_SIGN1, 0>(p, g, stream);
+        }
+    }
+    if (p.encoding == ENC_SQ2) {
+        switch (p.nw) {
+#define QV_CASE(W) case W: return launch_beam_search_w<ENC_SQ2, W>(p, g, stream);
+            QV_SM_WIDTHS(QV_CASE)
+#undef QV_CASE
+            default: return launch_beam_search_w<ENC_SQ2, 0>(p, g, stream);
+        }
+    }
     switch (p.nw) {
 #define QV_CASE(W) case W: return launch_beam_search_w<ENC_SM, W>(p, g, stream);
         QV_SM_WIDTHS(QV_CASE)

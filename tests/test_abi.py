@@ -62,7 +62,9 @@ def test_build_script_compiles_every_width_the_dispatcher_names():
     from paper_2605_02171_amd import build
     sm = sorted(w for e, w in build.SEARCH_VARIANTS if e == 0 and w != 0)
     assert sm == _compiled_widths()
-    assert {(1, 0), (1, 12), (2, 0), (2, 12), (0, 0)} <= set(build.SEARCH_VARIANTS)
+    for e in (1, 2):
+        assert sorted(w for enc, w in build.SEARCH_VARIANTS if enc == e and w != 0) == sm
+    assert {(0, 0), (1, 0), (2, 0)} <= set(build.SEARCH_VARIANTS)
 
 
 def test_recommended_code_layout(lib):
@@ -87,7 +89,7 @@ def test_recommended_code_layout(lib):
     assert [layout(d, 0) for d in (64, 128, 192, 300, 384, 448, 512, 768, 960, 1024, 1100, 1536, 2048, 3072, 4096)] == \
         [(1, 2), (2, 4), (4, 8), (6, 16), (6, 16), (8, 16), (8, 16), (12, 24), (16, 32), (16, 32), (24, 48), (24, 48),
          (32, 64), (48, 96), (64, 128)]
-    assert [layout(d, 1) for d in (64, 192, 384, 700, 768, 960)] == [(1, 1), (3, 4), (6, 8), (12, 16), (12, 16), (15, 16)]
+    assert [layout(d, 1) for d in (64, 192, 384, 700, 768, 960)] == [(1, 1), (4, 4), (6, 8), (12, 16), (12, 16), (16, 16)]
     assert [layout(d, 2) for d in (384, 700, 768)] == [(6, 16), (12, 24), (12, 24)]
     pw, st = ctypes.c_int(0), ctypes.c_int(0)
     assert f(0, 0, ctypes.byref(pw), ctypes.byref(st)) == -3 and f(70000, 0, ctypes.byref(pw), ctypes.byref(st)) == -3
@@ -99,9 +101,8 @@ def test_recommended_code_layout(lib):
             nw = (d + 63) // 64
             pw, stride = layout(d, enc)
             assert nw <= pw <= nw + nw // 2 + 2 and 3 * pw <= 4 * nw or pw == nw
-            if enc == 0:
-                nxt = next((w for w in widths if w >= nw), 0)
-                assert pw == (nxt if nxt and 3 * nxt <= 4 * nw else nw)
+            nxt = next((w for w in widths if w >= nw), 0)               # the three encodings share the compiled widths
+            assert pw == (nxt if nxt and 3 * nxt <= 4 * nw else nw)
             row = planes * pw
             assert stride >= row and (stride == row or stride % 2 == 0) and stride <= 4 * row + 16
             dense, chosen = mean_lines(row * 8, row * 8), mean_lines(row * 8, stride * 8)

@@ -104,7 +104,10 @@ def _search_both(qv, enc, x, q, adj, entry, k, ef, visit_cap=300):
 
 @pytest.mark.parametrize("enc", ENCODINGS)
 @pytest.mark.parametrize("d,R,ef,k", [(100, 10, 5, 5), (128, 32, 64, 10), (200, 70, 65, 10), (768, 64, 32, 10),
-                                      (768, 64, 300, 10), (1024, 64, 64, 10), (130, 130, 600, 7)])
+                                      (768, 64, 300, 10), (1024, 64, 64, 10), (130, 130, 600, 7),
+                                      # the other widths the kernels are compiled for
+                                      (256, 32, 64, 10), (384, 64, 64, 10), (512, 64, 48, 10), (1536, 32, 64, 10),
+                                      (2048, 16, 32, 5), (3072, 16, 32, 5)])
 def test_search_random_graphs_bit_exact(qv, enc, d, R, ef, k):
     rng = np.random.default_rng(d * 1000 + R + enc)
     n, nq = 3000, 37
@@ -139,7 +142,9 @@ def _sorted_rows(adj):
 @pytest.mark.parametrize("enc", ENCODINGS)
 @pytest.mark.parametrize("n,d,R,L,alpha,entry", [(1500, 128, 16, 32, 1.2, 7), (600, 128, 64, 128, 1.2, 11),
                                                  (300, 768, 16, 48, 1.2, 299), (2500, 100, 8, 16, 1.0, 5),
-                                                 (800, 300, 16, 32, 1.2, 3), (500, 40, 8, 16, 1.2, 0)])
+                                                 (800, 300, 16, 32, 1.2, 3), (500, 40, 8, 16, 1.2, 0),
+                                                 (400, 384, 16, 32, 1.2, 1), (300, 1024, 16, 32, 1.2, 2),
+                                                 (200, 1536, 12, 32, 1.2, 0), (200, 900, 12, 24, 1.2, 5)])
 def test_build_matches_oracle(qv, enc, n, d, R, L, alpha, entry):
     rng = np.random.default_rng(n + d + enc)
     x = rng.standard_normal((n, d)).astype(np.float32)
@@ -158,8 +163,8 @@ def test_argument_errors(qv):
     with pytest.raises(qv.QuiverError) as e:
         qv.encode(x, enc=7)
     assert e.value.code == -1
-    codes = torch.zeros((10, 26), dtype=torch.int64, device="cuda")   # 2-bit codes of d = 800: no construction kernel that wide
+    codes = torch.zeros((10, 50), dtype=torch.int64, device="cuda")   # 2-bit codes of d = 1600: no construction kernel that wide
     with pytest.raises(qv.QuiverError) as e:
-        qv.build_graph(codes, 800, 8, 16, 1.2, 0, enc=qv.ENC_SQ2)
+        qv.build_graph(codes, 1600, 8, 16, 1.2, 0, enc=qv.ENC_SQ2)
     assert e.value.code == -9
     assert qv.code_words(768, qv.ENC_SIGN1) == 12 and qv.code_words(768, qv.ENC_SQ2) == 24 and qv.code_words(768, 9) == 0
