@@ -219,10 +219,11 @@ int qv_build_graph(const uint64_t* codes, int64_t n, int d, int R, int L, double
  *    QV_ENC_SIGN1  "1-bit sign": the sign plane alone, qv_code_words_enc(d) = ceil(d/64) words per vector;
  *                  distance = number of differing signs.
  *    QV_ENC_SQ2    "2-bit SQ": every dimension falls into one of four equal-width buckets, distance = sum of
- *                  |level_a - level_b| (L1).  The paper names no range; here it is the vector's own value range:
- *                  level = number of k in {1, 2, 3} with 4 (x - min) >= k (max - min), evaluated in IEEE double in
- *                  this form (a constant vector has level 3 everywhere).  Two bit-planes, low bit of the level
- *                  first, packed like the Sign-Magnitude planes.
+ *                  |level_a - level_b| (L1).  The paper names no range; here it is [-2 tau, +2 tau] with tau the
+ *                  vector's exact mean magnitude (edges at -tau, 0, +tau; values beyond the range fall into the
+ *                  outer buckets), the range with which the quantiser ranks as Table 10 reports it: level 3 iff
+ *                  x > tau, 2 iff 0 < x <= tau, 1 iff -tau <= x <= 0, 0 iff x < -tau.  Two bit-planes, low bit of
+ *                  the level first, packed like the Sign-Magnitude planes.
  * qv_index_set_encoding tells an index which encoding its `codes` are in (queries are then encoded the same way).
  * Widths: encode, distance, scan and search take any d (the search kernel is compiled for the same plane widths in all
  * three encodings; at widths other than 768-d the ablation encodings use the default number of lanes per row whatever

@@ -223,27 +223,39 @@ static int encode_sign1(const float *x, int d, uint64_t *code) {
     return ORC_OK;
 }
 
-static int sq2_level(float x, float mn, float mx) {
-    double width = (double)mx - (double)mn;
-    double t = ((double)x - (double)mn) * 4.0;
-    int level = 0;
-    if (t >= width) level++;
-    if (t >= 2.0 * width) level++;
-    if (t >= 3.0 * width) level++;
-    return level;
-}
-
+/*
+ * 2-bit uniform scalar quantiser of the ablation (Sec. 5.5: "four equal-width buckets", L1 distance on the bucket
+ * indices).  The paper does not say which range the buckets divide.  Reading taken: like the method's own
+ * threshold, the range comes from the vector itself and needs no training data: [-2 tau, +2 tau] with tau the exact
+ * mean magnitude, i.e. bucket edges at -tau, 0, +tau, values beyond the range falling into the outer buckets.
+ * (With this range the quantiser ranks slightly better than the Sign-Magnitude code and both clearly better than the
+ * sign alone -- the order Table 10 reports; a range of [min, max] of the vector ranks worse than the sign alone.)
+ * An element equal to an edge goes with the tests of Sec. 3.1, which are strict: level 3 iff x > tau, level 2 iff
+ * 0 < x <= tau, level 1 iff -tau <= x <= 0, level 0 iff x < -tau.
+ * Planes: low bit of the level, then high bit.
+ */
 static int encode_sq2(const float *x, int d, uint64_t *code) {
     int W = (d + 63) / 64;
-    for (int w = 0; w < 2 * W; ++w) code[w] = 0;
-    float mn = x[0], mx = x[0];
+    big_t S;
+    big_zero(&S);
     for (int i = 0; i < d; ++i) {
-        if (!isfinite(x[i])) return ORC_ERR_NONFINITE;
-        if (x[i] < mn) mn = x[i];
-        if (x[i] > mx) mx = x[i];
+        uint32_t m;
+        int sh;
+        if (!split_abs(x[i], &m, &sh)) return ORC_ERR_NONFINITE;
+        big_add_shifted(&S, m, sh); /* S = sum_j |x_j| = D * tau, exact */
     }
+    for (int w = 0; w < 2 * W; ++w) code[w] = 0;
     for (int i = 0; i < d; ++i) {
-        int level = sq2_level(x[i], mn, mx);
+        uint32_t m = 0;
+        int sh = 0;
+        split_abs(x[i], &m, &sh);
+        big_t T; /* D * |x_i| */
+        big_zero(&T);
+        big_add_shifted(&T, (uint64_t)m * (uint64_t)d, sh);
+        int beyond = big_cmp(&T, &S) > 0; /* |x_i| > tau */
+        int level;
+        if (x[i] > 0.0f) level = beyond ? 3 : 2;
+        else level = beyond ? 0 : 1;
         if (level & 1) code[i / 64] |= (uint64_t)1 << (i % 64);
         if (level & 2) code[W + i / 64] |= (uint64_t)1 << (i % 64);
     }

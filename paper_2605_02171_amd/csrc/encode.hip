@@ -260,47 +260,25 @@ __global__ __launch_bounds__(64 * ENC_WAVES) void encode_sign1_kernel(const floa
     if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
 }
 
-// 2-bit uniform quantiser: four equal-width buckets over the vector's own range [min, max] (the paper names no
-// range; this is the reading taken).  level = number of k in {1, 2, 3} with 4 (x - min) >= k (max - min), every
-// difference and product in IEEE double in exactly this form, so that any implementation gets the same bits; a
-// constant vector has level 3 everywhere.  Planes: low bit of the level, then high bit.
-__global__ __launch_bounds__(64 * ENC_WAVES) void encode_sq2_kernel(const float* __restrict__ x, int64_t n, int d,
-                                                                    uint64_t* __restrict__ codes,
-                                                                    uint32_t* __restrict__ status) {
-    const int lane = threadIdx.x & 63;
-    const int64_t v = (int64_t)blockIdx.x * ENC_WAVES + (threadIdx.x >> 6);
-    if (v >= n) return;
+// 2-bit uniform quantiser of the paper's ablation (Sec. 5.5, Table 10; the paper names "four equal-width buckets" but no
+// range).  Reading taken: the range is [-2 tau, +2 tau] with tau the vector's exact mean magnitude, so the bucket
+// edges are -tau, 0, +tau; level 3 iff x > tau, 2 iff 0 < x <= tau, 1 iff -tau <= x <= 0, 0 iff x < -tau (the strict
+// tests of Sec. 3.1).  These are the two decisions of the Sign-Magnitude code, so the levels follow from its planes
+// (p = positive, s = strong): high bit = p, low bit = not (p xor s).  The kernel rewrites a Sign-Magnitude code row in
+// place: planes become low bit, then high bit; bits of dimensions >= d stay 0.  One thread per plane word.
+__global__ __launch_bounds__(256) void sq2_from_sm_kernel(uint64_t* __restrict__ codes, int64_t n, int d) {
     const int W = (d + 63) >> 6;
-    const float* xv = x + v * (int64_t)d;
-    float mn = xv[0], mx = xv[0];
-    bool finite = true;
-    for (int i = lane; i < d; i += 64) {
-        const float xi = xv[i];
-        finite &= (__float_as_uint(xi) & 0x7F800000u) != 0x7F800000u;
-        mn = xi < mn ? xi : mn;
-        mx = xi > mx ? xi : mx;
+    const int64_t total = n * W;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t row = i / W;
+        const int w = (int)(i - row * W);
+        uint64_t* r = codes + row * (2 * W);
+        const uint64_t p = r[w], s = r[W + w];
+        const int live = d - (w << 6);   // dimensions this word holds
+        const uint64_t mask = live >= 64 ? ~0ull : ((1ull << live) - 1ull);
+        r[w] = ~(p ^ s) & mask;
+        r[W + w] = p;
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const float a = __shfl_xor(mn, off), b = __shfl_xor(mx, off);
-        mn = a < mn ? a : mn;
-        mx = b > mx ? b : mx;
-    }
-    const bool all_finite = __all(finite);
-    const double lo = (double)mn, width = (double)mx - (double)mn;
-    const double w2 = 2.0 * width, w3 = 3.0 * width;
-    for (int w = 0; w < W; ++w) {
-        const int i = (w << 6) + lane;
-        int level = 0;
-        if (i < d) {
-            const double t = ((double)xv[i] - lo) * 4.0;
-            level = (t >= width ? 1 : 0) + (t >= w2 ? 1 : 0) + (t >= w3 ? 1 : 0);
-        }
-        const uint64_t lw = __ballot(level & 1), hw = __ballot(level & 2);
-        if (lane == 0) codes[v * (int64_t)(2 * W) + w] = lw;
-        if (lane == 1) codes[v * (int64_t)(2 * W) + W + w] = hw;
-    }
-    if (status && lane == 0) status[v] = all_finite ? 0u : QV_STATUS_NONFINITE_BIT;
 }
 
 // out[p] = distance of code rows ia[p] (in a) and ib[p] (in b) under the given encoding: one thread per pair
@@ -484,8 +462,12 @@ hipError_t launch_encode(const float* x, int64_t n, int d, int encoding, uint64_
         hipLaunchKernelGGL(encode_sign1_kernel, grid, block, 0, stream, x, n, d, codes, status);
         return hipGetLastError();
     }
-    if (encoding == ENC_SQ2) {
-        hipLaunchKernelGGL(encode_sq2_kernel, grid, block, 0, stream, x, n, d, codes, status);
+    if (encoding == ENC_SQ2) {   // the Sign-Magnitude decisions first, then their rewrite into levels
+        hipError_t e = launch_encode(x, n, d, ENC_SM, codes, status, stream);
+        if (e != hipSuccess) return e;
+        int64_t blocks = (n * ((d + 63) / 64) + 255) / 256;
+        if (blocks > 256 * 64) blocks = 256 * 64;
+        hipLaunchKernelGGL(sq2_from_sm_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, codes, n, d);
         return hipGetLastError();
     }
     // vectors per wave, measured at 1M vectors: 64 x W dimensions of 4 (256-d: 0.168 against 0.191 ms with one) and

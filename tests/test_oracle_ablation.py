@@ -54,28 +54,53 @@ def test_sign1_distance_is_the_hamming_distance():
 
 
 def test_sq2_levels_of_hand_worked_vectors():
-    # min 0, max 4: bucket width 1 -> 0, 1, 2, 3 and the maximum itself falls into the last bucket
-    x = np.array([[0, 1, 2, 3, 4], [-1, -0.5, 0, 0.49, 1], [7, 7, 7, 7, 7], [0, 0.99, 1.0, 2.99, 4]], dtype=np.float32)
-    lv = _levels(oracle.encode(x, enc=SQ2), 5)
-    assert lv[0].tolist() == [0, 1, 2, 3, 3]
-    assert lv[1].tolist() == [0, 1, 2, 2, 3]     # width 0.5 -> edges at -0.5, 0, 0.5 (an edge belongs to the upper bucket)
-    assert lv[2].tolist() == [3, 3, 3, 3, 3]     # constant vector: the reading puts every element into the top bucket
-    assert lv[3].tolist() == [0, 0, 1, 2, 3]
+    # edges at -tau, 0, +tau with tau the mean magnitude (the reading taken for "four equal-width buckets")
+    x = np.array([[0.9, -0.1, 0.2, -0.6],       # tau = 0.45
+                  [0.5, -0.5, 0.5, -0.5],       # tau = 0.5: an element on an outer edge stays in the inner bucket
+                  [0.0, -0.0, 3.0, -1.0],       # tau = 1: zero is "not positive"; -1 sits on the edge -tau
+                  [7.0, 7.0, 7.0, 7.0]], dtype=np.float32)
+    lv = _levels(oracle.encode(x, enc=SQ2), 4)
+    assert lv[0].tolist() == [3, 1, 2, 0]
+    assert lv[1].tolist() == [2, 1, 2, 1]
+    assert lv[2].tolist() == [1, 1, 3, 1]
+    assert lv[3].tolist() == [2, 2, 2, 2]        # constant vector: nothing exceeds the mean
 
 
-def test_sq2_scaling_by_powers_of_two_and_reflection():
+def test_sq2_levels_are_equal_width_buckets_of_the_range_plus_minus_two_tau():
+    # away from the edges the level is floor((x + 2 tau) / tau) clamped to 0..3, with tau from exact rationals
+    from fractions import Fraction
     rng = np.random.default_rng(3)
+    for d in (7, 64, 130):
+        x = rng.standard_normal((20, d)).astype(np.float32)
+        x[:, 0] *= 8.0                           # beyond the range: outer bucket
+        lv = _levels(oracle.encode(x, enc=SQ2), d)
+        for r in range(20):
+            fr = [Fraction(float(v)) for v in x[r]]
+            tau = sum(abs(f) for f in fr) / d
+            want = [min(3, max(0, int((f + 2 * tau) // tau))) for f in fr]
+            on_edge = [f in (-tau, 0, tau) for f in fr]
+            assert not any(on_edge)
+            assert lv[r].tolist() == want
+
+
+def test_sq2_scaling_reflection_and_relation_to_the_sign_magnitude_code():
+    rng = np.random.default_rng(4)
     d = 96
-    # integers of the form 4r + 1: every product below is exact and no value sits on a bucket edge
-    x = (4 * rng.integers(-250, 250, size=(30, d)) + 1).astype(np.float32)
-    x[:, 0], x[:, 1] = -1003.0, 1001.0           # fixed range: width 2004, edges at -502, -1, 500 (never 1 mod 4)
+    x = rng.standard_normal((30, d)).astype(np.float32)
     c = oracle.encode(x, enc=SQ2)
     assert (oracle.encode(x * 4.0, enc=SQ2) == c).all()
     assert (oracle.encode(x * 0.125, enc=SQ2) == c).all()
     lv, lv_neg = _levels(c, d), _levels(oracle.encode(-x, enc=SQ2), d)
-    assert (lv + lv_neg == 3).all()              # mirror image: bucket b becomes bucket 3 - b
-    want = np.clip(np.floor((x + 1003.0) / 501.0), 0, 3).astype(int)
-    assert (lv == want).all()
+    assert (lv + lv_neg == 3).all()              # mirror image (no zeros in x): bucket b becomes bucket 3 - b
+    # the two decisions are those of the method's own code: positive -> upper half, strong -> outer bucket
+    sm = oracle.encode(x)
+    W = (d + 63) // 64
+    pos = np.array([[(int(r[i // 64]) >> (i % 64)) & 1 for i in range(d)] for r in sm[:, :W]])
+    strong = np.array([[(int(r[i // 64]) >> (i % 64)) & 1 for i in range(d)] for r in sm[:, W:]])
+    assert (lv == np.where(pos == 1, 2 + strong, 1 - strong)).all()
+    assert (c[:, W - 1] >> np.uint64(d % 64) == 0).all() and (c[:, 2 * W - 1] >> np.uint64(d % 64) == 0).all()   # padding bits stay zero
+    frac = np.bincount(lv.ravel(), minlength=4) / lv.size
+    assert abs(frac[0] - frac[3]) < 0.03 and abs(frac[1] - frac[2]) < 0.03 and 0.18 < frac[3] < 0.25   # erfc(1/sqrt(pi))/2 = 0.212
 
 
 def test_sq2_distance_is_l1_on_levels_and_a_metric():
@@ -200,4 +225,5 @@ def test_more_bits_rank_closer_to_the_exact_ranking():
         ids, _ = oracle.bq_scan(oracle.encode(x, enc=enc), oracle.encode(q, enc=enc), w.d, 10, threads=4, enc=enc)
         overlap[enc] = oracle.topk_overlap(ids, exact)
     assert overlap[SIGN1] < overlap[SM]
+    assert overlap[SIGN1] < overlap[SQ2]         # Table 10's order: both 2-bit codes rank better than the sign alone
     assert min(overlap.values()) > 0.2
