@@ -28,6 +28,7 @@ namespace qv {
 constexpr uint64_t B_NONE = ~0ull;
 constexpr int BUF = 256;       // candidate keys (dist << 32 | id) a wave can sort
 constexpr int MAX_NEW = 192;   // new in-edge candidates a node considers per batch
+constexpr int N_BUCKETS = 1024;
 
 __device__ __forceinline__ void bsync() {
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
@@ -140,6 +141,13 @@ struct BuildParams {
     uint32_t* tgt_start;        // [n]    where the target's sources start in `sources`
     uint32_t* edge_start;       // [bs*R] for the edge of rank 0 at a target: tgt_start and ...
     uint32_t* edge_count;       // [bs*R] ... tgt_count of that target (what the reverse step needs, next to the edge)
+    // order of the reverse step: targets bucketed by id range (N_BUCKETS ranges of 2^bkt_shift ids), so that waves
+    // running at the same time work on neighbouring rows of the adjacency and of the codes
+    uint32_t* edge_bpos;        // [bs*R] for the edge of rank 0 at a target: its position inside the target's bucket
+    uint32_t* bkt_count;        // [N_BUCKETS] targets per bucket; 0 between batches
+    uint32_t* bkt_offset;       // [N_BUCKETS + 1] where each bucket starts in owner_list; last entry: number of targets
+    uint32_t* owner_list;       // [bs*R] edges of rank 0, bucket by bucket
+    int bkt_shift;
     uint32_t* sources;          // [bs*R] sources, one segment per target
     uint32_t* cursor;           // [1]    words of `sources` reserved so far; 0 between batches
 };
@@ -199,6 +207,25 @@ __global__ __launch_bounds__(256) void reserve_segments_kernel(BuildParams p, in
     p.tgt_start[b] = start;
     p.edge_start[e] = start;
     p.edge_count[e] = count;
+    p.edge_bpos[e] = atomicAdd(p.bkt_count + min(b >> p.bkt_shift, (uint32_t)(N_BUCKETS - 1)), 1u);
+}
+
+// one workgroup: exclusive prefix sum over the bucket counts (which it clears for the next batch)
+__global__ __launch_bounds__(N_BUCKETS) void bucket_offsets_kernel(BuildParams p) {
+    __shared__ uint32_t sums[N_BUCKETS];
+    const int t = threadIdx.x;
+    const uint32_t mine = p.bkt_count[t];
+    p.bkt_count[t] = 0;
+    sums[t] = mine;
+    __syncthreads();
+    for (int off = 1; off < N_BUCKETS; off <<= 1) {
+        const uint32_t add = t >= off ? sums[t - off] : 0u;
+        __syncthreads();
+        sums[t] += add;
+        __syncthreads();
+    }
+    p.bkt_offset[t] = sums[t] - mine;
+    if (t == N_BUCKETS - 1) p.bkt_offset[N_BUCKETS] = sums[t];
 }
 
 // one thread per edge: the source (batch node e / R) goes to its place in the target's segment
@@ -208,7 +235,9 @@ __global__ __launch_bounds__(256) void scatter_sources_kernel(BuildParams p, int
     if (e == 0) *p.cursor = 0;                           // every segment is reserved by now; the next batch starts at 0
     const uint32_t b = p.edge_target[e];
     if (b == EMPTY_ID) return;
-    p.sources[p.tgt_start[b] + p.edge_rank[e]] = (uint32_t)(p.done + e / p.R);
+    const uint32_t rank = p.edge_rank[e];
+    p.sources[p.tgt_start[b] + rank] = (uint32_t)(p.done + e / p.R);
+    if (rank == 0) p.owner_list[p.bkt_offset[min(b >> p.bkt_shift, (uint32_t)(N_BUCKETS - 1))] + p.edge_bpos[e]] = (uint32_t)e;
 }
 
 template <int ENC, int NW_T>
@@ -217,9 +246,9 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p) {
     __shared__ uint32_t sel[64];
     __shared__ uint32_t rowcopy[64];
     const int lane = threadIdx.x;
-    const int64_t e0 = blockIdx.x;
+    if (blockIdx.x >= p.bkt_offset[N_BUCKETS]) return;   // one workgroup per target of the batch, in bucket order
+    const int64_t e0 = p.owner_list[blockIdx.x];         // the edge of rank 0 at that target
     const uint32_t b = p.edge_target[e0];
-    if (b == EMPTY_ID || p.edge_rank[e0] != 0) return;   // only the edge of rank 0 works on its target
     const int64_t n_src = p.edge_count[e0];
     const uint32_t* src = p.sources + p.edge_start[e0];
     if (lane == 0) p.tgt_count[b] = 0;                   // left as the next batch expects it
@@ -285,10 +314,11 @@ __global__ __launch_bounds__(64) void reverse_kernel(BuildParams p) {
 // start of a construction: every adjacency slot empty, no edges counted at any target (a kernel, not memset nodes:
 // the whole call may be captured into a graph)
 __global__ void fill_empty_kernel(uint32_t* __restrict__ adj, int64_t words, uint32_t* __restrict__ tgt_count, int64_t n,
-                                  uint32_t* __restrict__ cursor) {
+                                  uint32_t* __restrict__ cursor, uint32_t* __restrict__ bkt_count) {
     const int64_t at = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, step = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = at; i < words; i += step) adj[i] = EMPTY_ID;
     for (int64_t i = at; i < n; i += step) tgt_count[i] = 0;
+    for (int64_t i = at; i < N_BUCKETS; i += step) bkt_count[i] = 0;
     if (at == 0) *cursor = 0;
 }
 
@@ -313,6 +343,8 @@ static hipError_t launch_batch(const BuildParams& bp, hipStream_t stream) {
     const int64_t n_edges = bp.bs * bp.R;
     const dim3 per_edge((unsigned)((n_edges + 255) / 256));
     hipLaunchKernelGGL(reserve_segments_kernel, per_edge, dim3(256), 0, stream, bp, n_edges);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(bucket_offsets_kernel, dim3(1), dim3(N_BUCKETS), 0, stream, bp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(scatter_sources_kernel, per_edge, dim3(256), 0, stream, bp, n_edges);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -357,8 +389,8 @@ static size_t padded_codes_bytes(int64_t n, int nw, int encoding) {
 
 size_t build_workspace_bytes(int64_t n, int nw, int encoding, int R, int L, int64_t max_batch) {
     const int64_t mb = build_max_batch(n, max_batch);
-    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 4) * 5 +
-           up256((size_t)n * 4) * 2 + 256 + padded_codes_bytes(n, nw, encoding) + 256;
+    return up256((size_t)mb * L * 4) * 2 + up256((size_t)mb * 4) * 2 + up256((size_t)mb * R * 4) * 7 +
+           up256((size_t)n * 4) * 2 + 256 + up256((size_t)(2 * N_BUCKETS + 1) * 4) + padded_codes_bytes(n, nw, encoding) + 256;
 }
 
 hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, int R, int L, double alpha, uint32_t entry,
@@ -388,12 +420,16 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     uint32_t* edge_count = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * R * 4);
     uint32_t* tgt_count = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)n * 4);
     uint32_t* tgt_start = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)n * 4);
+    uint32_t* edge_bpos = reinterpret_cast<uint32_t*>(ws);    ws += up256((size_t)mb * R * 4);
+    uint32_t* owner_list = reinterpret_cast<uint32_t*>(ws);   ws += up256((size_t)mb * R * 4);
+    uint32_t* bkt_count = reinterpret_cast<uint32_t*>(ws);
+    uint32_t* bkt_offset = bkt_count + N_BUCKETS;             ws += up256((size_t)(2 * N_BUCKETS + 1) * 4);
     uint32_t* cursor = reinterpret_cast<uint32_t*>(ws);
 
     {
         const int64_t words = n * (int64_t)R;
         const unsigned blocks = (unsigned)((words + 256 * 8 - 1) / (256 * 8) < 256 * 16 ? (words + 256 * 8 - 1) / (256 * 8) : 256 * 16);
-        hipLaunchKernelGGL(fill_empty_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, adj, words, tgt_count, n, cursor);
+        hipLaunchKernelGGL(fill_empty_kernel, dim3(blocks > 0 ? blocks : 1), dim3(256), 0, stream, adj, words, tgt_count, n, cursor, bkt_count);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -408,6 +444,9 @@ hipError_t build_graph(const uint64_t* codes, int64_t n, int d, int encoding, in
     bp.cand_ids = cand_ids; bp.cand_dist = cand_dist; bp.n_cand = n_cand;
     bp.edge_target = edge_target; bp.edge_rank = edge_rank; bp.sources = sources; bp.tgt_count = tgt_count;
     bp.tgt_start = tgt_start; bp.cursor = cursor; bp.edge_start = edge_start; bp.edge_count = edge_count;
+    bp.edge_bpos = edge_bpos; bp.owner_list = owner_list; bp.bkt_count = bkt_count; bp.bkt_offset = bkt_offset;
+    bp.bkt_shift = 0;
+    while (((int64_t)N_BUCKETS << bp.bkt_shift) < n) bp.bkt_shift++;
     for (int64_t done = 0; done < n;) {
         int64_t bs = done / 50;
         if (bs < 1) bs = 1;
