@@ -268,8 +268,7 @@ int qv_index_set_encoding(qv_index* index, int encoding);
  *                                        is reported as status bit QV_STATUS_TIMEOUT with an empty result.
  *                    The two in-kernel forms apply to ef <= 128 and vectors in device memory; elsewhere the stage runs
  *                    as a kernel of its own.
- *                    0: QV_RERANK_TAIL where a code row is at most 128 bytes long (d <= 512 for the 2-bit codes),
- *                       QV_RERANK_SEPARATE otherwise. */
+ *                    0: QV_RERANK_TAIL wherever it applies (the fastest form at every width measured). */
 #define QV_VISITED_EXACT 1
 #define QV_VISITED_CACHE 2
 #define QV_RERANK_SEPARATE 1

@@ -338,7 +338,8 @@ static int rerank_place(const qv_index* index, int ef, int row_words) {
     const bool in_kernel_ok = ef <= 128 && index->vecs_on_device;
     if (!in_kernel_ok || index->rerank_mode == QV_RERANK_SEPARATE) return QV_RERANK_SEPARATE;
     if (index->rerank_mode != 0) return index->rerank_mode;
-    return row_words * 8 <= 128 ? QV_RERANK_TAIL : QV_RERANK_SEPARATE;
+    (void)row_words;
+    return QV_RERANK_TAIL;
 }
 
 int qv_index_rerank_fused(const qv_index* index, int ef) {
@@ -462,13 +463,12 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     if (sp.vis_regions == 0 && sp.vis_slots > 8192) {  // 32-bit entries: keep the table within 32 KB of LDS
         qv::plan_visited_table(sp, 8192, false, cache);
     }
-    // Stage 2 inside the search launch (beams of up to 128 entries over vectors in device memory): by default where a
-    // code row is at most one 128-byte line, by other waves of the launch that start when the last searches are under
-    // way (QV_RERANK_TAIL).  Measured per 10,000 queries, ef = 64, kernel of its own / by the searching wave / by other
-    // waves: 1M x 384: 1.21 / 1.16 / 1.12 ms, 1M x 512: 1.27 / 1.22 / 1.19; with longer rows the search already moves
-    // lines as fast as the memory system does and nothing is gained (1M x 768: 1.26 / 1.33 / 1.25 ms), so there the
-    // stage stays a kernel of its own.  Inside the launch, the final lists leave it only if the caller's trace asks
-    // for them or other waves need them.
+    // Stage 2 inside the search launch (beams of up to 128 entries over vectors in device memory), by default by other
+    // waves of the launch that start when the last searches are under way (QV_RERANK_TAIL).  Measured per 10,000
+    // queries, ef = 64, kernel of its own / by the searching wave / by other waves: 1M x 384: 1.21 / 1.16 / 1.12 ms,
+    // 1M x 512: 1.27 / 1.22 / 1.19, 1M x 768: 1.24 / 1.33 / 1.23, 5M x 1024: 2.12 / - / 2.10, 1M x 3072: 4.63 / 4.92 /
+    // 4.37.  Inside the launch, the final lists leave it only if the caller's trace asks for them or other waves need
+    // them.
     int place = rerank_place(index, ef, planes * plane_words);
     if (place == QV_RERANK_TAIL && nq > (1ll << 30)) place = QV_RERANK_FUSED;   // two workgroups per query must fit a grid
     const bool fused = place != QV_RERANK_SEPARATE, tail = place == QV_RERANK_TAIL;

@@ -147,6 +147,28 @@ def test_host_side_argument_errors(lib):
     assert lib.qv_search(h, fake, 1, 1, 8, fake, fake, fake, 16, None, None) == -6             # too small
     assert lib.qv_search(h, None, 1, 1, 8, fake, fake, fake, 1 << 20, None, None) == -2
     assert lib.qv_search(h, None, 0, 1, 8, None, None, None, 0, None, None) == 0               # empty batch
+    # the entry point with built-in scratch: same argument checks, and its own limit, all before any device call
+    lib.qv_search_static.argtypes = [P, P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, P, P, P, P]
+    assert lib.qv_search_static(None, fake, 1, 1, 8, fake, fake, None, None) == -2
+    assert lib.qv_search_static(h, fake, 1, 9, 8, fake, fake, None, None) == -4
+    assert lib.qv_search_static(h, fake, 1, 1, 5000, fake, fake, None, None) == -5
+    assert lib.qv_search_static(h, fake, 0, 1, 8, None, None, None, None) == 0
+    assert lib.qv_search_static(h, fake, 10_000_000, 1, 8, fake, fake, None, None) == -10
+    # split layout: only for the widths the kernel is compiled for; pointers checked
+    w1, w2 = ctypes.c_int(0), ctypes.c_int(0)
+    lib.qv_split_layout.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    assert lib.qv_split_layout(768, ctypes.byref(w1), ctypes.byref(w2)) == 0 and (w1.value, w2.value) == (16, 8)
+    assert lib.qv_split_layout(1024, ctypes.byref(w1), ctypes.byref(w2)) == 0 and (w1.value, w2.value) == (16, 16)
+    assert lib.qv_split_layout(1536, ctypes.byref(w1), ctypes.byref(w2)) == 0 and (w1.value, w2.value) == (32, 16)
+    assert lib.qv_split_layout(384, ctypes.byref(w1), ctypes.byref(w2)) == -9
+    assert lib.qv_split_layout(0, ctypes.byref(w1), ctypes.byref(w2)) == -3 and lib.qv_split_layout(768, None, None) == -2
+    lib.qv_split_codes.argtypes = [P, ctypes.c_int64, ctypes.c_int, P, P, P]
+    assert lib.qv_split_codes(fake, 5, 384, fake, fake, None) == -9 and lib.qv_split_codes(None, 5, 768, fake, fake, None) == -2
+    assert lib.qv_split_codes(fake, -1, 768, fake, fake, None) == -1 and lib.qv_split_codes(None, 0, 768, None, None, None) == 0
+    lib.qv_index_set_split_codes.argtypes = [P, P, P]
+    assert lib.qv_index_set_split_codes(None, fake, fake) == -2
+    assert lib.qv_index_set_split_codes(h, fake, fake) == -9          # the test index is 8-d
+    assert lib.qv_index_set_split_codes(h, None, None) == 0
     lib.qv_index_set_tuning.argtypes = [P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     assert lib.qv_index_set_tuning(h, 512, 0, 0, 0, 0) == -1 and lib.qv_index_set_tuning(h, 0, 3, 0, 0, 0) == -1
     assert lib.qv_index_set_tuning(h, 0, 0, 16, 0, 0) == -1 and lib.qv_index_set_tuning(h, 8192, 4, 32, 0, 0) == 0

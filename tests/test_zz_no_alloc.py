@@ -69,8 +69,8 @@ def _both(lib, index, q, k, ef, cap=200):
     return got
 
 
-@pytest.mark.parametrize("d,R,fused", [(768, 64, False), (384, 32, True)])
-def test_static_scratch_search_equals_workspace_search_twice_in_a_row(lib, d, R, fused):
+@pytest.mark.parametrize("d,R,rerank_mode", [(768, 64, 1), (384, 32, 2), (384, 32, 0), (768, 64, 3)])
+def test_static_scratch_search_equals_workspace_search_twice_in_a_row(lib, d, R, rerank_mode):
     rng = np.random.default_rng(d)
     n = 20_000
     x = torch.from_numpy(rng.standard_normal((n, d)).astype(np.float32)).cuda()
@@ -81,7 +81,7 @@ def test_static_scratch_search_equals_workspace_search_twice_in_a_row(lib, d, R,
     index = P()
     assert lib.qv_index_load(ctypes.byref(index), n, d, R, adj.data_ptr(), codes.data_ptr(), x.data_ptr(), 3) == 0
     try:
-        assert lib.qv_index_set_tuning(index, 0, 0, 0, 0, 2 if fused else 1) == 0
+        assert lib.qv_index_set_tuning(index, 0, 0, 0, 0, rerank_mode) == 0   # where Stage 2 runs: 0 = default
         big = torch.from_numpy(rng.standard_normal((5000, d)).astype(np.float32)).cuda()
         small = torch.from_numpy(rng.standard_normal((37, d)).astype(np.float32)).cuda()
         util.note(f"static scratch: d={d} first call, 5000 queries, ef=64")
