@@ -602,6 +602,10 @@ def test_search_split_code_layout_is_bit_exact(qv, d, R, ef, k, n):
             out = qv.search(index, qd, k, ef, trace=True, visit_cap=1300)
             torch.cuda.synchronize()
             _assert_search_equal(qv, ref, out, exact_counters=False)
+    index.set_tuning(0, 0, 32, 0, 0)              # 32-bit visited entries, everything else by default
+    out = qv.search(index, qd, k, ef, trace=True, visit_cap=1300)
+    torch.cuda.synchronize()
+    _assert_search_equal(qv, ref, out, exact_counters=False)
     index.set_split_codes(None)
     index.set_tuning(0, 0, 0, qv.VISITED_EXACT)
     out = qv.search(index, qd, k, ef, trace=True, visit_cap=1300)
