@@ -127,3 +127,27 @@ def test_pairs_entry_point():
     out = oracle.sm_distance_pairs(a, ia, b, ib, d)
     for p in range(0, 300, 7):
         assert out[p] == pyref.distance_by_levels(a[ia[p]], b[ib[p]], d)
+
+
+def test_sign_plane_gives_a_lower_bound_of_the_distance():
+    # Table 1: a dimension with differing signs costs (1 + strong_a)(1 + strong_b) >= (1 + strong_a).  So the distance
+    # with b's magnitude bits taken as zero -- all of them, or all but a known prefix -- never exceeds the distance,
+    # and equals it when every magnitude bit is known.  (The library's split code layout reads b's magnitude words
+    # only where this bound does not already decide.)
+    rng = np.random.default_rng(21)
+    d = 200
+    W = (d + 63) // 64
+    x = rng.standard_normal((40, d)).astype(np.float32)
+    c = oracle.encode(x)
+    for i in range(0, 40, 3):
+        for j in range(1, 40, 4):
+            full = oracle.sm_distance(c[i], c[j], d)
+            assert full == pyref.distance_by_levels(c[i], c[j], d)
+            previous = -1
+            for known in range(W + 1):                      # magnitude words of b that are known
+                masked = c[j].copy()
+                masked[W + known:] = 0
+                bound = oracle.sm_distance(c[i], masked, d)
+                assert previous <= bound <= full            # more known words never loosen the bound
+                previous = bound
+            assert previous == full
