@@ -67,8 +67,8 @@ def ground_truth(xd, qd, k, metric):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
     ap.add_argument("--nq", type=int, default=0)
