@@ -69,7 +69,7 @@ struct qv_index {
     int lanes_per_row;  // <= 0: choose from d
     int table_format;   // 0: 16-bit visited entries when the graph is small enough; 32: always 32-bit
     int visited_mode;   // 0: choose from ef; QV_VISITED_EXACT; QV_VISITED_CACHE
-    int rerank_mode;    // 0: choose; QV_RERANK_SEPARATE; QV_RERANK_FUSED
+    int rerank_mode;    // 0: choose; QV_RERANK_SEPARATE; QV_RERANK_FUSED; QV_RERANK_TAIL
     bool vecs_on_device;  // false: the float32 vectors live in host memory the device can address
     int encoding;       // QV_ENC_*: what `codes` holds and what the queries are encoded to
     int code_plane_words;  // 64-bit words per bit-plane as stored in `codes`; 0: ceil(d / 64)
@@ -334,19 +334,15 @@ int qv_index_set_split_codes(qv_index* index, const uint64_t* split1, const uint
 }
 
 // Where Stage 2 runs for this beam width: QV_RERANK_SEPARATE, QV_RERANK_FUSED or QV_RERANK_TAIL (see quiver.h).
-static int rerank_place(const qv_index* index, int ef, int row_words) {
+static int rerank_place(const qv_index* index, int ef) {
     const bool in_kernel_ok = ef <= 128 && index->vecs_on_device;
     if (!in_kernel_ok || index->rerank_mode == QV_RERANK_SEPARATE) return QV_RERANK_SEPARATE;
-    if (index->rerank_mode != 0) return index->rerank_mode;
-    (void)row_words;
-    return QV_RERANK_TAIL;
+    return index->rerank_mode != 0 ? index->rerank_mode : QV_RERANK_TAIL;
 }
 
 int qv_index_rerank_fused(const qv_index* index, int ef) {
     if (!index) return QV_ERR_NULL;
-    const int planes = index->encoding == QV_ENC_SIGN1 ? 1 : 2;
-    const int pw = index->code_stride > 0 ? index->code_plane_words : (index->d + 63) / 64;
-    return rerank_place(index, ef, planes * pw) != QV_RERANK_SEPARATE ? 1 : 0;
+    return rerank_place(index, ef) != QV_RERANK_SEPARATE ? 1 : 0;
 }
 
 size_t qv_search_workspace_bytes(int64_t nq, int d, int k, int ef) {
@@ -374,7 +370,8 @@ int static_scratch(void** out) {
     if (!g_scratch_ptr[dev]) {
         void* ptr = nullptr;
         e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
-        if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch) gave no address");
         g_scratch_ptr[dev] = ptr;
     }
     *out = g_scratch_ptr[dev];
@@ -471,7 +468,7 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     // 1M x 512: 1.27 / 1.22 / 1.19, 1M x 768: 1.24 / 1.33 / 1.23, 5M x 1024: 2.12 / - / 2.10, 1M x 3072: 4.63 / 4.92 /
     // 4.37.  Inside the launch, the final lists leave it only if the caller's trace asks for them or other waves need
     // them.
-    int place = rerank_place(index, ef, planes * plane_words);
+    int place = rerank_place(index, ef);
     if (place == QV_RERANK_TAIL && nq > (1ll << 30)) place = QV_RERANK_FUSED;   // two workgroups per query must fit a grid
     const bool fused = place != QV_RERANK_SEPARATE, tail = place == QV_RERANK_TAIL;
     // the final lists go straight into the caller's trace buffers when there are any

@@ -62,3 +62,16 @@ def test_nothing_committed_reads_the_scratch_folder_or_the_reference():
     for f in ("bench.py", "__graft_entry__.py"):
         text = open(os.path.join(ROOT, f)).read()
         assert "_work/" not in text and "/root/reference" not in text, f
+
+
+def test_the_library_allocates_no_device_memory():
+    """Every buffer is the caller's (inputs, outputs, workspaces) or, for qv_search_static, an array inside the
+    library's own device code: no source of the library calls an allocating HIP routine."""
+    allocating = re.compile(r"\bhip(Ext)?(Malloc|Free|HostMalloc|HostAlloc|HostFree|MallocAsync|FreeAsync|MallocManaged|"
+                            r"MallocFromPoolAsync|MallocWithFlags|MemPoolCreate|HostRegister)\w*\s*\(")
+    for path in _sources(os.path.join("paper_2605_02171_amd", "csrc"), (".hip", ".h")):
+        code = re.sub(r"//[^\n]*", "", open(path).read())
+        assert not allocating.search(code), path
+    api = open(os.path.join(ROOT, "paper_2605_02171_amd", "csrc", "api.hip")).read()
+    assert "static __device__ __align__(256) unsigned char scratch[QV_STATIC_SCRATCH_BYTES]" in api
+    assert "hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))" in api
