@@ -4,12 +4,13 @@
 // Mapping to gfx950: one 64-lane wavefront per query, one wavefront per workgroup.
 //   * candidate list ("pool"): ef sorted 64-bit keys held in registers, entry e in lane e%64,
 //     register e/64.  key = dist << 33 | id << 1 | expanded, so integer order is (dist, id) order.
-//   * visited set: bucketed table of ids in LDS (one 16-byte bucket per probe, LDS compare-and-swap to
-//     claim a slot; 16-bit tags that identify an id exactly, or 32-bit ids).  By default it is a small
-//     cache in which new ids displace old ones, so that 16 queries fit a compute unit; a forgotten
-//     node that comes up again is evaluated again, which cannot change the list (see merge_new_keys)
-//     and is reported in the status word.  The other mode never forgets and stops taking ids when
-//     nearly full.
+//   * visited set: bucketed table of ids in LDS (one 16-byte bucket per probe; 16-bit tags that identify
+//     an id exactly, or 32-bit ids).  By default it is a small cache in which new ids displace old ones,
+//     so that 16 queries fit a compute unit (16-bit tags: seven per bucket, placed in turn by a counter
+//     in the bucket that one LDS atomic add advances, no retry); a forgotten node that comes up again is
+//     evaluated again, which cannot change the list (see merge_new_keys) and is reported in the status
+//     word.  The other mode never forgets (slots claimed by LDS compare-and-swap) and stops taking ids
+//     when nearly full.
 //   * expansion: lane j reads adj[u][j] (one coalesced row; the row of the runner-up is loaded one
 //     expansion ahead), lanes filter their ids through the visited table, survivors are compacted
 //     into LDS, then G lanes cooperate on one neighbour's code: lane s of a group loads words s,
@@ -183,11 +184,13 @@ __device__ __forceinline__ bool visited16_test_and_set(uint32_t* tab32, uint32_t
 
 // ---------------------------------------------------------------------------------------------
 // Visited set as a cache (the other mode of the same two table formats): an id is looked up and kept
-// in its home bucket only; when the bucket has no free slot the id takes the place of another one
-// (slot chosen by `clock`), which is thereby forgotten and may be evaluated again later -- harmless
-// for the list (see merge_new_keys), cheaper in LDS.  Lookup and insertion stay exact for the ids that
-// are in the table: two lanes holding the same id race on the same word and exactly one of them wins.
-// Returns true when v was not in the table; `evicted` is raised when an id was displaced.
+// in its home bucket only; when the bucket has no free slot the id takes the place of another one,
+// which is thereby forgotten and may be evaluated again later -- harmless for the list (see
+// merge_new_keys), cheaper in LDS.  A lookup never reports an id that was not put in (entries identify
+// ids exactly), and an id that is still in its bucket is always found.
+// Both return true when v was not in the table; `evicted` is raised when an id was displaced.
+// 32-bit entries: four ids per bucket; a slot is claimed by compare-and-swap (two lanes that want the same
+// slot: exactly one wins, the other looks again), the victim of a full bucket is chosen by `clock`.
 __device__ __forceinline__ bool visited32_cache(uint32_t* tab, int bucket_bits, uint32_t v, uint32_t clock,
                                                 bool& evicted) {
     uint32_t* bp = tab + ((v * 2654435761u) >> (32 - bucket_bits)) * 4;
@@ -205,12 +208,22 @@ __device__ __forceinline__ bool visited32_cache(uint32_t* tab, int bucket_bits, 
     }
 }
 
-__device__ __forceinline__ bool visited16_cache(uint32_t* tab32, uint32_t regions, uint32_t B, uint32_t v, uint32_t clock,
-                                                bool active, bool& evicted) {
-    // Straight-line body, repeated while any lane of the wave lost a compare-and-swap (two ids of one expansion
-    // that want the same slot: usual, since some sixty ids go into a few hundred buckets); lanes that are done,
-    // or were never `active`, are masked.  Ends: a failed compare-and-swap means another lane's succeeded, and a
-    // lane stops at its first success.
+// 16-bit entries: a bucket (16 bytes) holds seven tags and, in the upper half of its last word, the number of tags
+// ever put into it.  A lookup reads the bucket and compares seven halves; an id that is not there takes the next
+// position in turn (count mod 7: first the free ones, then the oldest tag), which it learns from one atomic add on the
+// counter -- lanes of one expansion that fall into the same bucket get different counts, so there is no retry loop.
+// An adjacency row may name a node twice: both lanes then miss, and the one with the higher count gives way before
+// anything is written (the loop below runs once per lane that was not the first of this call in its bucket, a handful
+// per expansion).
+// Called by all lanes of the wave that are active at the call site (it holds wave-level operations).
+typedef unsigned short qv_u16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t min_halves(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(qv_u16x2, a), __builtin_bit_cast(qv_u16x2, b)));
+}
+constexpr uint32_t CACHE16_EMPTY_LAST_WORD = 0x0000FFFFu;   // no tag in the seventh place, count 0
+
+__device__ __forceinline__ bool visited16_cache(uint32_t* tab32, uint32_t regions, uint32_t B, uint32_t v, bool active,
+                                                int lane, bool& evicted) {
     const uint32_t r0 = v / 65535u;
     const uint32_t t0 = v - r0 * 65535u;
     uint32_t r = r0 + ((((t0 * 40503u) & 0xFFFFu) * regions) >> 16);
@@ -218,28 +231,26 @@ __device__ __forceinline__ bool visited16_cache(uint32_t* tab32, uint32_t region
     const uint32_t hb = (((v * 2654435761u) >> 16) * B) >> 16;
     const uint32_t pat = t0 * 0x00010001u;
     uint32_t* bp = tab32 + (r * B + hb) * 4;
-    const uint32_t victim = (clock >> 1) & 3u;
-    bool fresh = false, pending = active;
-    while (__any(pending)) {
-        uint4 s = make_uint4(0u, 0u, 0u, 0u);
-        if (pending) s = *reinterpret_cast<const uint4*>(bp);
-        const bool hit = (any_zero_half(s.x ^ pat) | any_zero_half(s.y ^ pat) | any_zero_half(s.z ^ pat) |
-                          any_zero_half(s.w ^ pat)) != 0u;
-        // first word with a free half, else the victim word
-        const uint32_t free_words = (any_zero_half(~s.x) ? 1u : 0u) | (any_zero_half(~s.y) ? 2u : 0u) |
-                                    (any_zero_half(~s.z) ? 4u : 0u) | (any_zero_half(~s.w) ? 8u : 0u);
-        const bool full = free_words == 0u;
-        const uint32_t e = full ? victim : (uint32_t)__builtin_ctz(free_words | 16u);
-        const uint32_t word = e == 0 ? s.x : (e == 1 ? s.y : (e == 2 ? s.z : s.w));
-        const bool low_half = full ? !(clock & 1u) : (word & 0xFFFFu) == 0xFFFFu;
-        const uint32_t want = low_half ? ((word & 0xFFFF0000u) | t0) : ((word & 0xFFFFu) | (t0 << 16));
-        const bool tries = pending && !hit;
-        uint32_t old = ~word;
-        if (tries) old = atomicCAS(bp + e, word, want);
-        const bool won = tries && old == word;
-        fresh |= won;
-        evicted |= won && full;
-        pending = tries && !won;
+    uint4 s = make_uint4(0u, 0u, 0u, 0u);
+    if (active) s = *reinterpret_cast<const uint4*>(bp);
+    // a half of s equal to the tag shows as a zero half of s ^ pat; the counter's half is kept from ever matching
+    const uint32_t x = min_halves(min_halves(s.x ^ pat, s.y ^ pat), min_halves(s.z ^ pat, (s.w ^ pat) | 0xFFFF0000u));
+    bool fresh = active && any_zero_half(x) == 0u;
+    const uint32_t before = s.w >> 16;   // the bucket's count when this call began (every lane reads before any lane adds)
+    uint32_t count = before;
+    if (fresh) count = atomicAdd(bp + 3, 0x00010000u) >> 16;
+    uint64_t later = __ballot(fresh && count != before);
+    while (later) {
+        const int j = __ffsll((unsigned long long)later) - 1;
+        later &= later - 1;
+        const uint32_t vj = (uint32_t)__builtin_amdgcn_readlane((int)v, j);
+        const uint32_t cj = (uint32_t)__builtin_amdgcn_readlane((int)count, j);
+        const bool twin_before = __any(fresh && v == vj && count < cj);   // same id => same bucket => comparable counts
+        if (twin_before && lane == j) fresh = false;                     // (its turn in the bucket stays unused)
+    }
+    if (fresh) {
+        reinterpret_cast<uint16_t*>(bp)[count % 7u] = (uint16_t)t0;
+        evicted |= count >= 7u;
     }
     return fresh;
 }
@@ -637,8 +648,9 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
     uint64_t* skeys = reinterpret_cast<uint64_t*>(dlist + 64);  // [64*P + 64] merge scatter area
     uint64_t* qlds = skeys + 64 * P + 64;                      // [3*NW] query words (generic path)
 
+    const uint32_t last_word = (NARROW && cache_mode) ? CACHE16_EMPTY_LAST_WORD : EMPTY_ID;
     for (uint32_t i = lane * 4; i < tab_words; i += 256)
-        *reinterpret_cast<uint4*>(tab + i) = make_uint4(EMPTY_ID, EMPTY_ID, EMPTY_ID, EMPTY_ID);
+        *reinterpret_cast<uint4*>(tab + i) = make_uint4(EMPTY_ID, EMPTY_ID, EMPTY_ID, last_word);
 
     constexpr int RPP = 64 / G;  // neighbour rows per pass
     constexpr int KW = NW_T > 0 ? (NW_T + G - 1) / G : 1;
@@ -916,7 +928,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
         list[0] = p.entry;
         bool ignore = false;
         if (cache_mode) {
-            if constexpr (NARROW) visited16_cache(tab, vis_regions, vis_B, p.entry, 0u, true, ignore);
+            if constexpr (NARROW) visited16_cache(tab, vis_regions, vis_B, p.entry, true, lane, ignore);
             else visited32_cache(tab, bucket_bits, p.entry, 0u, ignore);
         } else {
             if constexpr (NARROW) visited16_test_and_set(tab, vis_regions, vis_B, p.entry, true, ignore);
@@ -974,7 +986,7 @@ __global__ __launch_bounds__(64) void beam_search_kernel(SearchParams p) {
             if (cache_mode) {
                 bool evicted = false;
                 if constexpr (NARROW) {
-                    fresh = visited16_cache(tab, vis_regions, vis_B, valid ? v : 0u, n_exp + (uint32_t)lane, valid, evicted);
+                    fresh = visited16_cache(tab, vis_regions, vis_B, valid ? v : 0u, valid, lane, evicted);
                 } else {
                     if (valid) fresh = visited32_cache(tab, bucket_bits, v, n_exp + (uint32_t)lane, evicted);
                 }

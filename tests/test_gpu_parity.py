@@ -253,6 +253,33 @@ def test_search_tiny_visited_cache_keeps_results_exact(qv, table_format, slots, 
     _assert_search_equal(qv, ref, out, exact_counters=False)
 
 
+@pytest.mark.parametrize("table_format", [0, 32])
+def test_search_rows_that_name_nodes_several_times(qv, table_format):
+    # adjacency rows drawn with replacement from a few nodes: most rows name a node two, three or more times, in
+    # places that fall into the same expansion; the second occurrence must not be evaluated (counts equal the
+    # oracle's wherever the cache forgot nothing) and must never reach the list twice
+    rng = np.random.default_rng(404)
+    n, d, R = 4000, 256, 64
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((50, d)).astype(np.float32)
+    near = rng.integers(0, n, size=(n, 40))
+    adj = np.take_along_axis(near, rng.integers(0, 40, size=(n, R)), axis=1).astype(np.uint32)
+    assert max(len(set(r.tolist())) for r in adj[:200]) < R - 15
+    codes = oracle.encode(x, threads=8)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.encode(xd), xd, 9)
+    for ef in (4, 64, 200):
+        ref = oracle.search(q, adj, codes, x, 9, min(10, ef), ef, visit_cap=600, threads=8)
+        for mode in (qv.VISITED_CACHE, qv.VISITED_EXACT):
+            index.set_tuning(0, 0, table_format, mode)
+            out = qv.search(index, torch.from_numpy(q).cuda(), min(10, ef), ef, trace=True, visit_cap=600)
+            torch.cuda.synchronize()
+            _assert_search_equal(qv, ref, out, exact_counters=False)
+            if ef == 4:   # few enough insertions that the cache forgets nothing for many queries (a repeated node uses
+                # up places in its bucket, so the flag comes early on such rows): their counts were compared above
+                assert ((qv.to_numpy_u32(out.status) & 2) == 0).mean() > 0.2
+
+
 def test_search_visited_cache_on_a_graph_with_many_parts(qv):
     # 500,000 nodes: the 16-bit cache is cut into eight parts of 64 buckets at the default 4096 slots
     rng = np.random.default_rng(78)
