@@ -246,7 +246,8 @@ int qv_index_set_encoding(qv_index* index, int encoding);
 
 /* Tunables of the search kernel (defaults picked from the shape when 0).  Host only.
  *    visited_slots   slots of the per-query visited table, 1024..28672 (rounded up to a multiple of 1024; to a
- *                    power of two and at most 8192 with 32-bit entries)
+ *                    power of two and at most 8192 with 32-bit entries; as a cache of 16-bit entries every eighth
+ *                    slot is a counter, so 7/8 of the slots hold ids)
  *    lanes_per_row   lanes that share one neighbour's code during the gather (1, 2, 4, 8 or 16)
  *    table_format    0: 16-bit visited-table entries whenever the graph is small enough for them, else 32-bit;
  *                    32: always 32-bit entries
