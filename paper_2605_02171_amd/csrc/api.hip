@@ -449,10 +449,11 @@ int qv_search(const qv_index* index, const float* queries, int64_t nq, int k, in
     // degree 64), as far as 64 KB of LDS per query allow.
     const bool cache = index->visited_mode != QV_VISITED_EXACT;
     // (wider beams: the merge area grows to 8.7 KB at ef = 1024, so the cache shrinks to keep the queries per CU up;
-    // measured optima at 1M x 768: 3072 slots for ef 129..512, 1024 beyond)
+    // measured optima at 1M x 768: 3072 slots for ef 129..512, 2048 beyond -- ef = 1024: 26.2 / 25.1 / 28.4 / 27.7 ms
+    // per 10,000 queries with 1024 / 2048 / 3072 / 4096 slots, 74 / 61 / 52 / 45 % of the nodes evaluated again)
     // (short rows, planes of up to 6 words: the kernel needs few enough registers for a fifth wave per SIMD, which a
     // 3072-slot cache lets LDS hold: 1M x 384, ef = 64: 1.00 -> 0.98 ms per batch at 1 % more evaluations)
-    const int cache_slots = ef <= 128 ? (plane_words <= 6 ? 3072 : 4096) : (ef <= 512 ? 3072 : 1024);
+    const int cache_slots = ef <= 128 ? (plane_words <= 6 ? 3072 : 4096) : (ef <= 512 ? 3072 : 2048);
     int slots = index->visited_slots > 0 ? index->visited_slots : (cache ? cache_slots : 96 * ef + 2048);
     const size_t fixed = qv::beam_search_lds_bytes(sp.nw, 0, true, ef);
     const int max_narrow = (int)((65536 - fixed) / 2 / 1024 * 1024);
