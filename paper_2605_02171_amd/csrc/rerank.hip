@@ -28,6 +28,20 @@ __device__ __forceinline__ bool ranks_before(float sa, uint32_t ia, float sb, ui
     return sa > sb || (sa == sb && ia < ib);
 }
 
+// (score, id) as one integer whose order is the ranking order: larger = earlier (score descending, then id
+// ascending).  Floats map to integers of the same order (negative zero counts as zero, as in ranks_before);
+// no key is 0, which stands for "no candidate".
+__device__ __forceinline__ uint64_t rank_key(float s, uint32_t id) {
+    uint32_t u = __float_as_uint(s + 0.0f);
+    u ^= (u >> 31) ? 0xFFFFFFFFu : 0x80000000u;
+    return ((uint64_t)u << 32) | (uint32_t)~id;
+}
+__device__ __forceinline__ float score_of_rank_key(uint64_t key) {
+    uint32_t u = (uint32_t)(key >> 32);
+    u ^= (u >> 31) ? 0x80000000u : 0xFFFFFFFFu;
+    return __uint_as_float(u);
+}
+
 __global__ __launch_bounds__(RR_THREADS) void rerank_kernel(RerankParams p) {
     __shared__ float s_score[RR_MAX_EF];
     __shared__ uint32_t s_id[RR_MAX_EF];
@@ -81,6 +95,43 @@ __global__ __launch_bounds__(RR_THREADS) void rerank_kernel(RerankParams p) {
         }
     }
     __syncthreads();
+
+    // The best k.  Few out of many (k <= candidates / 16, e.g. 10 of 1,024): k rounds of "take the best that is
+    // left" -- every thread keeps its up to four candidates as sortable keys, a round is one maximum over the
+    // workgroup -- instead of ranking every candidate against all others, which at 1,024 candidates costs a million
+    // comparisons per query (a third of this kernel's time there).
+    if (p.k * 16 <= nc) {
+        __shared__ uint64_t s_best[2][RR_WAVES];
+        uint64_t mine[RR_MAX_EF / RR_THREADS];
+#pragma unroll
+        for (int i = 0; i < RR_MAX_EF / RR_THREADS; ++i) {
+            const int t = (int)threadIdx.x + i * RR_THREADS;
+            mine[i] = t < nc ? rank_key(s_score[t], s_id[t]) : 0ull;
+        }
+        for (int r = 0; r < p.k; ++r) {   // k <= nc here
+            uint64_t best = mine[0];
+#pragma unroll
+            for (int i = 1; i < RR_MAX_EF / RR_THREADS; ++i) best = mine[i] > best ? mine[i] : best;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const uint64_t other = __shfl_xor(best, off);
+                best = other > best ? other : best;
+            }
+            if (lane == 0) s_best[r & 1][wv] = best;   // two buffers: one barrier per round is enough
+            __syncthreads();
+            best = s_best[r & 1][0];
+#pragma unroll
+            for (int w = 1; w < RR_WAVES; ++w) best = s_best[r & 1][w] > best ? s_best[r & 1][w] : best;
+#pragma unroll
+            for (int i = 0; i < RR_MAX_EF / RR_THREADS; ++i)
+                if (mine[i] == best) mine[i] = 0ull;   // ids in a list are distinct, so keys are
+            if (threadIdx.x == 0) {
+                p.ids[q * (int64_t)p.k + r] = ~(uint32_t)best;
+                p.scores[q * (int64_t)p.k + r] = score_of_rank_key(best);
+            }
+        }
+        return;
+    }
 
     // rank by counting: position of candidate t = number of candidates that come before it
     for (int t = threadIdx.x; t < nc; t += RR_THREADS) {

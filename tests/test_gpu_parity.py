@@ -595,6 +595,57 @@ def test_rerank_puts_non_finite_stored_vectors_last(qv):
             util.assert_topk_matches(ids[:, :n - 3], scores[:, :n - 3], want_ids, want_scores)
 
 
+@pytest.mark.parametrize("ef,k", [(64, 1), (64, 4), (129, 8), (300, 10), (300, 18), (300, 19), (1024, 64), (1024, 65)])
+def test_rerank_kernel_takes_few_of_many_with_ties(qv, ef, k):
+    # Stage 2 as a kernel of its own picks a small k out of a long list in k rounds, a larger one by ranking all:
+    # both sides of that switch (k * 16 <= list length), on vectors that repeat (equal scores: the smaller id comes
+    # first), that point away from the query (negative scores), and with rows that hold NaN / Inf (they come last)
+    rng = np.random.default_rng(ef * 100 + k)
+    n, d, nq = 1100, 192, 21
+    base = rng.standard_normal((40, d)).astype(np.float32)
+    x = base[rng.integers(0, 40, size=n)] * rng.choice([1.0, -1.0, 2.0], size=(n, 1)).astype(np.float32)
+    q = (base[rng.integers(0, 40, size=nq)] + 0.05 * rng.standard_normal((nq, d))).astype(np.float32)
+    adj = np.stack([(np.arange(n) * 7 + s) % n for s in range(1, 33)], axis=1).astype(np.uint32)
+    codes = oracle.encode(x)
+    ref = oracle.search(q, adj, codes, x, 3, k, ef)
+    xd = torch.from_numpy(x).cuda()
+    index = qv.Index(qv.from_numpy_u32(adj), qv.from_numpy_u64(codes), xd, 3)
+    index.set_tuning(0, 0, 0, 0, qv.RERANK_SEPARATE)
+    out = qv.search(index, torch.from_numpy(q).cuda(), k, ef, trace=True)
+    torch.cuda.synchronize()
+    assert (qv.to_numpy_u32(out.cand_ids) == ref.cand_ids).all()
+    ids, scores = qv.to_numpy_u32(out.ids), out.scores.cpu().numpy()
+    util.assert_topk_matches(ids, scores, ref.ids, ref.scores)
+    # exact ties are decided by id: among the results of one query, equal scores come with ascending ids, and a
+    # list member left out at the k-th score has a larger id than the ones taken at that score
+    exact = x.astype(np.float64)
+    for i in range(nq):
+        assert (np.diff(scores[i]) <= 0).all()
+        for r in range(k - 1):
+            if scores[i][r] == scores[i][r + 1]:
+                assert ids[i][r] < ids[i][r + 1], (i, r)
+        members = ref.cand_ids[i][ref.cand_ids[i] != E]
+        left_out = np.setdiff1d(members, ids[i])
+        qq = q[i].astype(np.float64)
+        cos = exact[left_out] @ qq / (np.linalg.norm(exact[left_out], axis=1) * np.linalg.norm(qq))
+        assert (cos <= float(scores[i][-1]) * (1 + 2e-5 * np.sign(scores[i][-1])) + 1e-6).all()
+    # the same lists with three rows spoiled: they score -inf and come last, by id
+    dirty = x.copy()
+    spoiled = sorted(int(v) for v in ref.cand_ids[0][:3])
+    dirty[spoiled[0], 1], dirty[spoiled[1], 0], dirty[spoiled[2], d - 1] = np.nan, np.inf, -np.inf
+    index2 = qv.Index(qv.from_numpy_u32(adj), qv.from_numpy_u64(codes), torch.from_numpy(dirty).cuda(), 3)
+    index2.set_tuning(0, 0, 0, 0, qv.RERANK_SEPARATE)
+    k_all = min(ef, int(ref.n_cand[0]))
+    out2 = qv.search(index2, torch.from_numpy(q[:1]).cuda(), k_all, ef, trace=True)
+    torch.cuda.synchronize()
+    ids2, sc2 = qv.to_numpy_u32(out2.ids)[0], out2.scores.cpu().numpy()[0]
+    assert ids2[-3:].tolist() == spoiled and np.isneginf(sc2[-3:]).all() and np.isfinite(sc2[:-3]).all()
+    few = qv.search(index2, torch.from_numpy(q[:1]).cuda(), k, ef)
+    torch.cuda.synchronize()
+    keep = min(k, k_all - 3)
+    assert (qv.to_numpy_u32(few.ids)[0][:keep] == ids2[:keep]).all() and (few.scores.cpu().numpy()[0][:keep] == sc2[:keep]).all()
+
+
 @pytest.mark.parametrize("d,R,ef,k,n", [(768, 64, 64, 10, 20_000), (768, 64, 16, 10, 3_000), (768, 32, 200, 50, 20_000),
                                         (1024, 64, 64, 10, 8_000), (1536, 48, 100, 10, 5_000), (768, 70, 1024, 100, 9_000),
                                         (768, 64, 1, 1, 6_000)])
